@@ -1,0 +1,232 @@
+/*
+ * fdc - parallel decoding step for template-structured chain-of-thought on one
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * The library implements the forward pass in which every ready field of a CoT
+ * template decodes together (Sec. 3.3 of the FastDriveCoT paper): the new
+ * tokens of all ready fields are packed along the sequence dimension of one
+ * sequence, attend through a mask derived from the template's dependency graph
+ * (Eq. 1) to the shared prefix, to the written tokens of their ancestor fields
+ * and to their own earlier tokens, use position ids fixed by the per-field
+ * slot lengths, and share one KV cache in which padding is never written or
+ * read.  Which fields are ready is decided by the caller (Algorithm 1).
+ *
+ * Conventions
+ *  - every function returns 0 (FDC_OK) or a negative FDC_E* code; a message for
+ *    the last failure of the calling thread is available from fdc_last_error().
+ *  - "host" pointers are ordinary CPU memory, read or written before the call
+ *    returns.  "device" pointers are GPU memory owned by the caller; the
+ *    library allocates no device memory (the caller sizes buffers with the
+ *    *_bytes queries).  Device work is enqueued on the given hipStream_t
+ *    (passed as void*) and the call returns without synchronising.
+ *  - matrices handed in are bf16, row-major, [out_features][in_features];
+ *    a projection is y = x * W^T.  fdc_pack_weight() converts them once into
+ *    the tile order the kernels stream.
+ *  - rows of a step are ordered m = (scene * R + branch) * T + t.
+ *  - limits: n_fields <= 64 for a context; head_dim in {64, 128};
+ *    d_model, n_q_heads*head_dim and d_mlp multiples of 32; B*R*T <= 16 rows per
+ *    step for the dense projections (FDC_ECAP otherwise).
+ */
+#ifndef FDC_H
+#define FDC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FDC_OK       0
+#define FDC_EINVAL  (-1)  /* null pointer, bad size, misaligned pointer          */
+#define FDC_ECYCLE  (-2)  /* dependency graph is not acyclic                      */
+#define FDC_EORDER  (-3)  /* an edge points from a later field to an earlier one */
+#define FDC_ERANGE  (-4)  /* field id, slot offset or position out of range       */
+#define FDC_ECAP    (-5)  /* a size exceeds what the kernels are built for        */
+#define FDC_EHIP    (-6)  /* a HIP runtime call failed                            */
+#define FDC_ESTATE  (-7)  /* weights, cache or workspace not set                  */
+
+typedef struct fdc_ctx fdc_ctx;
+
+typedef struct fdc_model_desc {
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;   /* divides n_q_heads (grouped-query attention) */
+    int32_t head_dim;     /* 64 or 128 */
+    int32_t d_mlp;        /* SwiGLU inner width */
+    int32_t vocab;
+    float   rope_base;    /* rotary base; pair (i, i + head_dim/2) turns by pos * base^(-2i/head_dim) */
+    float   norm_eps;     /* RMSNorm epsilon */
+} fdc_model_desc;
+
+/* device pointers to one decoder layer's parameters */
+typedef struct fdc_layer_weights {
+    const float* g1;      /* [d_model] fp32 gain of the attention RMSNorm               */
+    const void*  wqkv;    /* packed [(Hq+2Hkv)*D][d_model]; rows: Q heads, K heads, V heads */
+    const void*  wo;      /* packed [d_model][Hq*D]                                      */
+    const float* g2;      /* [d_model] fp32 gain of the MLP RMSNorm                      */
+    const void*  wgu;     /* packed with mode FDC_PACK_GATE_UP from [2*d_mlp][d_model], gate rows first */
+    const void*  wd;      /* packed [d_model][d_mlp]                                     */
+} fdc_layer_weights;
+
+const char* fdc_strerror(int32_t code);
+const char* fdc_last_error(void);
+int32_t     fdc_version(void);
+
+/* ---------------------------------------------------------------------------
+ * Template -> mask metadata (host only; no GPU needed).  Sec. 3.3, Eq. 1:
+ * a token of field B may attend to tokens of field A iff a path of >= 1 edge
+ * leads from A to B.  Fixed slot lengths fix every position id.
+ *
+ *  slot_len [F]        host in   fixed length of each field's slot (>= 1)
+ *  edge_src/dst [E]    host in   direct dependencies src -> dst
+ *  anc_words [F*W]     host out  strict ancestors, bit (g%64) of word g/64 of
+ *                                row f, W = (F+63)/64
+ *  slot_start [F]      host out  prefix_len + sum of earlier slot lengths
+ *  level [F]           host out  longest-path depth, roots 0 (may be NULL)
+ *  total_len           host out  N = prefix_len + sum of slots
+ * Errors: FDC_EINVAL (null, F < 1, slot < 1, prefix < 0), FDC_ERANGE (edge names
+ * a field outside 0..F-1), FDC_ECYCLE, FDC_EORDER (src >= dst: the template order
+ * must be a topological order so that visible keys precede the query).
+ */
+int32_t fdc_build_mask(int32_t n_fields, const int32_t* slot_len,
+                       int32_t n_edges, const int32_t* edge_src, const int32_t* edge_dst,
+                       int32_t prefix_len,
+                       uint64_t* anc_words, int32_t* slot_start, int32_t* level,
+                       int32_t* total_len);
+
+/* Dense expansion of exactly the metadata the attention kernel consumes, for
+ * one scene (host only; test helper).  Row r is the token at offset
+ * row_off[r] of field row_field[r]; valid_len[g] is the number of tokens of
+ * field g in the cache after the step's appends.  mask[r*N + j] = 1 iff j is
+ * in the prefix, or a written token of a strict ancestor, or an own token at
+ * offset <= row_off[r] (Sec. 3.3: padding is invisible to everyone).
+ * pos[r] = slot_start[row_field[r]] + row_off[r].
+ */
+int32_t fdc_dense_mask(int32_t n_fields, const int32_t* slot_len, const int32_t* slot_start,
+                       const uint64_t* anc_words, int32_t prefix_len,
+                       const int32_t* valid_len,
+                       int32_t n_rows, const int32_t* row_field, const int32_t* row_off,
+                       uint8_t* mask, int32_t* pos);
+
+/* ---------------------------------------------------------------------------
+ * Weight packing.  Streams a row-major bf16 matrix [n_out][k_in] (device) into
+ * the 16x32-element tile order the projection kernels read with one contiguous
+ * 1 KiB load per wavefront.  n_out multiple of 16, k_in multiple of 32.
+ * FDC_PACK_GATE_UP interleaves the 16-row tiles of the gate half and the up
+ * half of a [2*d_mlp][d_model] matrix so SwiGLU can be applied in the
+ * projection's epilogue.  dst needs fdc_packed_weight_bytes(n_out, k_in) bytes
+ * (= 2*n_out*k_in) and must not overlap src.
+ */
+#define FDC_PACK_PLAIN   0
+#define FDC_PACK_GATE_UP 1
+size_t  fdc_packed_weight_bytes(int64_t n_out, int64_t k_in);
+int32_t fdc_pack_weight(const void* src_dev, void* dst_dev, int64_t n_out, int64_t k_in,
+                        int32_t mode, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Context: model shape + template + batch shape.  Validates the template like
+ * fdc_build_mask.  n_scenes = B; max_branches = largest R and max_tokens =
+ * largest T a step will use.
+ */
+int32_t fdc_create(const fdc_model_desc* model,
+                   int32_t n_fields, const int32_t* slot_len,
+                   int32_t n_edges, const int32_t* edge_src, const int32_t* edge_dst,
+                   int32_t prefix_len,
+                   int32_t n_scenes, int32_t max_branches, int32_t max_tokens,
+                   fdc_ctx** out);
+void    fdc_destroy(fdc_ctx* ctx);
+
+/* Bytes of the K cache (the V cache has the same size): all layers, all
+ * scenes, position-indexed (cache index == position id), N rounded up to a
+ * multiple of 32, bf16, stored in 32-key tiles in the operand order of the
+ * attention kernel's matrix instructions. */
+size_t  fdc_kv_cache_bytes(const fdc_ctx* ctx);
+size_t  fdc_workspace_bytes(const fdc_ctx* ctx);
+/* device buffers, 256-byte aligned; kept (not copied) until fdc_destroy */
+int32_t fdc_set_kv_cache(fdc_ctx* ctx, void* k_cache_dev, void* v_cache_dev);
+/* also uploads the template tables into the workspace on `stream` */
+int32_t fdc_set_workspace(fdc_ctx* ctx, void* workspace_dev, size_t bytes, void* stream);
+int32_t fdc_set_layer_weights(fdc_ctx* ctx, int32_t layer, const fdc_layer_weights* w);
+/* emb: device bf16 row-major [vocab][d_model] (gathered, not packed);
+ * gf: device fp32 [d_model] final-norm gain; lm: packed [vocab][d_model] */
+int32_t fdc_set_head_weights(fdc_ctx* ctx, const void* emb, const float* gf, const void* lm);
+
+/* valid_len[b*F + g] = number of tokens of field g of scene b in the cache.
+ * host arrays. fdc_reset zeroes them. */
+int32_t fdc_reset(fdc_ctx* ctx);
+int32_t fdc_set_valid_len(fdc_ctx* ctx, const int32_t* valid_len);
+int32_t fdc_get_valid_len(const fdc_ctx* ctx, int32_t* valid_len);
+
+/* ---------------------------------------------------------------------------
+ * Sec. 3.3 "KV cache fully shared and reused": write rows of K (already
+ * rotated) and V into layer `layer` of the cache at (scene, position).  Used in
+ * bulk to install prefix K/V and slot history; the decode step appends its own
+ * rows itself.  Does not change valid_len.
+ *  k_new, v_new   device bf16 [n_rows][Hkv][D]
+ *  row_scene/pos  device int32 [n_rows]; rows with scene < 0 are skipped.
+ *                 Out-of-range scene or position: the row is skipped and the
+ *                 call still returns FDC_OK (indices live on the device).
+ */
+int32_t fdc_kv_append(fdc_ctx* ctx, int32_t layer, const void* k_new, const void* v_new,
+                      const int32_t* row_scene, const int32_t* row_pos, int32_t n_rows,
+                      void* stream);
+
+/* ---------------------------------------------------------------------------
+ * One forward pass in which every listed branch decodes T tokens (Sec. 3.3;
+ * the loop body of Algorithm 1).  For each scene b and branch r:
+ * field = branch_field[b*R + r] (-1 = inactive entry), first new slot offset =
+ * branch_off[b*R + r].  All new K/V are appended (cache index = position id =
+ * slot_start[field] + offset) and valid_len is advanced before any row attends;
+ * inside a branch the T rows are causal.
+ *  branch_field/off host int32 [B*R]
+ *  tok_in      device int32 [B*R*T] input token ids, or NULL when emb_in given
+ *  emb_in      device bf16 [B*R*T][d_model] input rows, or NULL
+ *  tok_out     device int32 [B*R*T] greedy next token (lowest index among
+ *              maxima), -1 for inactive rows
+ *  gap_out     device fp32 [B*R*T] top-1 minus top-2 logit, or NULL
+ *  logits_out  device fp32 [B*R*T][vocab], or NULL
+ *  hidden_out  device fp32 [(L+2)][B*R*T][d_model], or NULL: residual stream
+ *              after the embedding (0) and after each layer (1..L), then the
+ *              final normalised hidden state (L+1)
+ * Errors: FDC_ESTATE, FDC_ECAP (R, T or rows above limits), FDC_ERANGE (field id,
+ * or offset + T beyond the slot), FDC_EINVAL, FDC_EHIP.  On error nothing is
+ * enqueued and valid_len is unchanged.
+ */
+int32_t fdc_parallel_decode_step(fdc_ctx* ctx, int32_t n_branches, int32_t T,
+                                 const int32_t* branch_field, const int32_t* branch_off,
+                                 const int32_t* tok_in, const void* emb_in,
+                                 int32_t* tok_out, float* gap_out,
+                                 float* logits_out, float* hidden_out, void* stream);
+
+/* The step's attention alone (Sec. 3.3 mask; "shared KV cache accessed by
+ * multiple query tokens within a single attention kernel"): DAG-masked GQA
+ * decode attention of the given rotated queries against layer `layer` of the
+ * cache under the current valid_len (which must already include the rows'
+ * own tokens; not advanced here).
+ *  q    device bf16 [B*R*T][Hq][D]
+ *  out  device fp32 [B*R*T][Hq*D]; rows of inactive branches are zero
+ */
+int32_t fdc_masked_attention(fdc_ctx* ctx, int32_t layer, const void* q,
+                             int32_t n_branches, int32_t T,
+                             const int32_t* branch_field, const int32_t* branch_off,
+                             float* out, void* stream);
+
+/* Per-row greedy argmax over fp32 logits (final logits are fp32, Sec. 4.1).
+ * logits device [M][ld] (ld >= V); idx_out device int32 [M]: lowest index of
+ * the maximum; top2_gap_out device fp32 [M] or NULL. */
+int32_t fdc_argmax(const float* logits, int32_t M, int32_t V, int64_t ld,
+                   int32_t* idx_out, float* top2_gap_out, void* stream);
+
+/* One dense projection y[M][n_out] = x[M][k_in] * W^T with W packed, x and y
+ * device fp32 row-major, M <= 16; `scratch` device, fdc_linear_scratch_bytes().
+ * Exposes the projection kernels of the step for tests and measurements. */
+size_t  fdc_linear_scratch_bytes(int32_t M, int64_t n_out, int64_t k_in);
+int32_t fdc_linear(const float* x, const void* w_packed, float* y,
+                   int32_t M, int64_t n_out, int64_t k_in, void* scratch, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDC_H */

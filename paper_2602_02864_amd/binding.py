@@ -1,0 +1,360 @@
+"""ctypes binding of libfdc.so.
+
+Argument marshalling only: every function here converts Python / numpy /
+torch arguments into the plain pointers and sizes of the C ABI declared in
+include/fdc.h and calls the entry point of the same name.  torch is used for
+device memory and the current HIP stream, nothing else; no step of the decode
+path is computed here.  If the library has not been built the import of the
+entry points fails loudly - there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfdc.so")
+
+FDC_OK, FDC_EINVAL, FDC_ECYCLE, FDC_EORDER, FDC_ERANGE, FDC_ECAP, FDC_EHIP, FDC_ESTATE = \
+    0, -1, -2, -3, -4, -5, -6, -7
+FDC_PACK_PLAIN, FDC_PACK_GATE_UP = 0, 1
+
+EXPORTS = [
+    "fdc_strerror", "fdc_last_error", "fdc_version", "fdc_build_mask", "fdc_dense_mask",
+    "fdc_packed_weight_bytes", "fdc_pack_weight", "fdc_create", "fdc_destroy",
+    "fdc_kv_cache_bytes", "fdc_workspace_bytes", "fdc_set_kv_cache", "fdc_set_workspace",
+    "fdc_set_layer_weights", "fdc_set_head_weights", "fdc_reset", "fdc_set_valid_len",
+    "fdc_get_valid_len", "fdc_kv_append", "fdc_parallel_decode_step", "fdc_masked_attention",
+    "fdc_argmax", "fdc_linear_scratch_bytes", "fdc_linear",
+]
+
+
+class FdcError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"fdc error {code}: {msg}")
+        self.code = code
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_mlp", C.c_int32),
+                ("vocab", C.c_int32), ("rope_base", C.c_float), ("norm_eps", C.c_float)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [("g1", C.c_void_p), ("wqkv", C.c_void_p), ("wo", C.c_void_p),
+                ("g2", C.c_void_p), ("wgu", C.c_void_p), ("wd", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libfdc.so (once) and declares the signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           f"`python -m paper_2602_02864_amd.build` (no fallback exists)")
+    L = C.CDLL(LIB_PATH)
+    i32, i64, vp, sz = C.c_int32, C.c_int64, C.c_void_p, C.c_size_t
+    pi32 = C.POINTER(C.c_int32)
+    L.fdc_strerror.restype = C.c_char_p
+    L.fdc_strerror.argtypes = [i32]
+    L.fdc_last_error.restype = C.c_char_p
+    L.fdc_last_error.argtypes = []
+    L.fdc_version.restype = i32
+    L.fdc_build_mask.restype = i32
+    L.fdc_build_mask.argtypes = [i32, pi32, i32, pi32, pi32, i32, C.POINTER(C.c_uint64), pi32, pi32, pi32]
+    L.fdc_dense_mask.restype = i32
+    L.fdc_dense_mask.argtypes = [i32, pi32, pi32, C.POINTER(C.c_uint64), i32, pi32, i32, pi32, pi32,
+                                 C.POINTER(C.c_uint8), pi32]
+    L.fdc_packed_weight_bytes.restype = sz
+    L.fdc_packed_weight_bytes.argtypes = [i64, i64]
+    L.fdc_pack_weight.restype = i32
+    L.fdc_pack_weight.argtypes = [vp, vp, i64, i64, i32, vp]
+    L.fdc_create.restype = i32
+    L.fdc_create.argtypes = [C.POINTER(ModelDesc), i32, pi32, i32, pi32, pi32, i32, i32, i32, i32,
+                             C.POINTER(vp)]
+    L.fdc_destroy.restype = None
+    L.fdc_destroy.argtypes = [vp]
+    L.fdc_kv_cache_bytes.restype = sz
+    L.fdc_kv_cache_bytes.argtypes = [vp]
+    L.fdc_workspace_bytes.restype = sz
+    L.fdc_workspace_bytes.argtypes = [vp]
+    L.fdc_set_kv_cache.restype = i32
+    L.fdc_set_kv_cache.argtypes = [vp, vp, vp]
+    L.fdc_set_workspace.restype = i32
+    L.fdc_set_workspace.argtypes = [vp, vp, sz, vp]
+    L.fdc_set_layer_weights.restype = i32
+    L.fdc_set_layer_weights.argtypes = [vp, i32, C.POINTER(LayerWeights)]
+    L.fdc_set_head_weights.restype = i32
+    L.fdc_set_head_weights.argtypes = [vp, vp, vp, vp]
+    L.fdc_reset.restype = i32
+    L.fdc_reset.argtypes = [vp]
+    L.fdc_set_valid_len.restype = i32
+    L.fdc_set_valid_len.argtypes = [vp, pi32]
+    L.fdc_get_valid_len.restype = i32
+    L.fdc_get_valid_len.argtypes = [vp, pi32]
+    L.fdc_kv_append.restype = i32
+    L.fdc_kv_append.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
+    L.fdc_parallel_decode_step.restype = i32
+    L.fdc_parallel_decode_step.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, vp, vp]
+    L.fdc_masked_attention.restype = i32
+    L.fdc_masked_attention.argtypes = [vp, i32, vp, i32, i32, pi32, pi32, vp, vp]
+    L.fdc_argmax.restype = i32
+    L.fdc_argmax.argtypes = [vp, i32, i32, i64, vp, vp, vp]
+    L.fdc_linear_scratch_bytes.restype = sz
+    L.fdc_linear_scratch_bytes.argtypes = [i32, i64, i64]
+    L.fdc_linear.restype = i32
+    L.fdc_linear.argtypes = [vp, vp, vp, i32, i64, i64, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> None:
+    if rc != FDC_OK:
+        raise FdcError(rc, lib().fdc_last_error().decode() or lib().fdc_strerror(rc).decode())
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32).reshape(-1))
+
+
+def _p(a: np.ndarray, ty=C.c_int32):
+    return a.ctypes.data_as(C.POINTER(ty))
+
+
+def _edges(edges):
+    e = np.asarray(list(edges), dtype=np.int32).reshape(-1, 2)
+    return np.ascontiguousarray(e[:, 0]), np.ascontiguousarray(e[:, 1])
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+# --------------------------------------------------------------------------- host only
+def fdc_build_mask(slot_len: Sequence[int], edges, prefix_len: int) -> dict:
+    sl = _i32(slot_len)
+    F = sl.size
+    src, dst = _edges(edges)
+    W = max(1, (F + 63) // 64)
+    anc = np.zeros((max(F, 1), W), dtype=np.uint64)
+    start = np.zeros(max(F, 1), dtype=np.int32)
+    level = np.zeros(max(F, 1), dtype=np.int32)
+    total = C.c_int32(0)
+    _check(lib().fdc_build_mask(F, _p(sl), src.size, _p(src), _p(dst), int(prefix_len),
+                                _p(anc, C.c_uint64), _p(start), _p(level), C.byref(total)))
+    return {"anc_words": anc, "slot_start": start, "level": level, "total_len": int(total.value)}
+
+
+def fdc_dense_mask(slot_len, slot_start, anc_words, prefix_len: int, valid_len, row_field, row_off):
+    sl, ss, vl = _i32(slot_len), _i32(slot_start), _i32(valid_len)
+    rf, ro = _i32(row_field), _i32(row_off)
+    anc = np.ascontiguousarray(np.asarray(anc_words, dtype=np.uint64))
+    N = int(ss[-1] + sl[-1])
+    mask = np.zeros((rf.size, N), dtype=np.uint8)
+    pos = np.zeros(rf.size, dtype=np.int32)
+    _check(lib().fdc_dense_mask(sl.size, _p(sl), _p(ss), _p(anc, C.c_uint64), int(prefix_len), _p(vl),
+                                rf.size, _p(rf), _p(ro), _p(mask, C.c_uint8), _p(pos)))
+    return mask, pos
+
+
+# --------------------------------------------------------------------------- device
+def fdc_packed_weight_bytes(n_out: int, k_in: int) -> int:
+    return int(lib().fdc_packed_weight_bytes(n_out, k_in))
+
+
+def fdc_pack_weight(src, mode: int = FDC_PACK_PLAIN):
+    """src: torch bf16 [n_out][k_in] on the GPU -> packed torch buffer (bf16, 1-D)."""
+    import torch
+    assert src.is_cuda and src.dtype == torch.bfloat16 and src.is_contiguous() and src.dim() == 2
+    n_out, k_in = src.shape
+    dst = torch.empty(fdc_packed_weight_bytes(n_out, k_in) // 2, dtype=torch.bfloat16, device=src.device)
+    _check(lib().fdc_pack_weight(src.data_ptr(), dst.data_ptr(), n_out, k_in, mode, _stream()))
+    return dst
+
+
+def fdc_argmax(logits, V: Optional[int] = None, want_gap: bool = True):
+    import torch
+    assert logits.is_cuda and logits.dtype == torch.float32 and logits.dim() == 2 and logits.is_contiguous()
+    M, ld = logits.shape
+    V = ld if V is None else V
+    idx = torch.empty(M, dtype=torch.int32, device=logits.device)
+    gap = torch.empty(M, dtype=torch.float32, device=logits.device) if want_gap else None
+    _check(lib().fdc_argmax(logits.data_ptr(), M, V, ld, idx.data_ptr(),
+                            gap.data_ptr() if want_gap else None, _stream()))
+    return idx, gap
+
+
+def fdc_linear(x, w_packed, n_out: int):
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.is_contiguous()
+    M, k_in = x.shape
+    nbytes = int(lib().fdc_linear_scratch_bytes(M, n_out, k_in))
+    if nbytes == 0:
+        raise FdcError(FDC_ECAP, "shape not supported by fdc_linear")
+    scratch = torch.zeros(nbytes, dtype=torch.uint8, device=x.device)
+    y = torch.empty(M, n_out, dtype=torch.float32, device=x.device)
+    _check(lib().fdc_linear(x.data_ptr(), w_packed.data_ptr(), y.data_ptr(), M, n_out, k_in,
+                            scratch.data_ptr(), _stream()))
+    return y
+
+
+class Context:
+    """Owns an fdc_ctx plus the torch buffers handed to it (cache, workspace,
+    packed weights).  Methods carry the names of the C entry points."""
+
+    def __init__(self, dims, slot_len, edges, prefix_len, n_scenes=1, max_branches=1, max_tokens=1,
+                 device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.dims = dims
+        self.desc = ModelDesc(dims.n_layers, dims.d_model, dims.n_q_heads, dims.n_kv_heads,
+                              dims.head_dim, dims.d_mlp, dims.vocab, dims.rope_base, dims.norm_eps)
+        self.slot_len = _i32(slot_len)
+        self.F = self.slot_len.size
+        self.B, self.Rmax, self.Tmax = n_scenes, max_branches, max_tokens
+        src, dst = _edges(edges)
+        self._h = C.c_void_p()
+        _check(lib().fdc_create(C.byref(self.desc), self.F, _p(self.slot_len), src.size, _p(src), _p(dst),
+                                int(prefix_len), n_scenes, max_branches, max_tokens, C.byref(self._h)))
+        self._keep = []
+        with torch.cuda.device(self.device):
+            kvb = int(lib().fdc_kv_cache_bytes(self._h))
+            self.k_cache = torch.zeros(kvb // 2, dtype=torch.bfloat16, device=self.device)
+            self.v_cache = torch.zeros(kvb // 2, dtype=torch.bfloat16, device=self.device)
+            _check(lib().fdc_set_kv_cache(self._h, self.k_cache.data_ptr(), self.v_cache.data_ptr()))
+            wsb = int(lib().fdc_workspace_bytes(self._h))
+            self.workspace = torch.empty(wsb, dtype=torch.uint8, device=self.device)
+            _check(lib().fdc_set_workspace(self._h, self.workspace.data_ptr(), wsb, _stream()))
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self.torch.cuda.synchronize(self.device)
+            lib().fdc_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- weights -------------------------------------------------------------------
+    def _dev_bf16(self, a):
+        """numpy uint16 bf16 patterns / fp32 values of bf16-representable numbers /
+        torch tensor -> contiguous torch bf16 tensor on the device."""
+        torch = self.torch
+        if isinstance(a, torch.Tensor):
+            return a.to(self.device, torch.bfloat16).contiguous()
+        a = np.asarray(a)
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(self.device).view(torch.bfloat16).contiguous()
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device).to(torch.bfloat16)
+
+    def _dev_f32(self, a):
+        torch = self.torch
+        if isinstance(a, torch.Tensor):
+            return a.to(self.device, torch.float32).contiguous()
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device)
+
+    def set_layer_weights(self, layer: int, w: dict):
+        """w: g1, wqkv, wo, g2, wgu, wd in the row-major [out][in] convention."""
+        g1, g2 = self._dev_f32(w["g1"]), self._dev_f32(w["g2"])
+        packed = {}
+        for k in ("wqkv", "wo", "wgu", "wd"):
+            src = self._dev_bf16(w[k])
+            packed[k] = fdc_pack_weight(src, FDC_PACK_GATE_UP if k == "wgu" else FDC_PACK_PLAIN)
+            del src
+        lw = LayerWeights(g1.data_ptr(), packed["wqkv"].data_ptr(), packed["wo"].data_ptr(),
+                          g2.data_ptr(), packed["wgu"].data_ptr(), packed["wd"].data_ptr())
+        _check(lib().fdc_set_layer_weights(self._h, layer, C.byref(lw)))
+        self._keep.append((g1, g2, packed))
+
+    def set_head_weights(self, emb, gf, lm):
+        e, g = self._dev_bf16(emb), self._dev_f32(gf)
+        lmp = fdc_pack_weight(self._dev_bf16(lm))
+        _check(lib().fdc_set_head_weights(self._h, e.data_ptr(), g.data_ptr(), lmp.data_ptr()))
+        self._keep.append((e, g, lmp))
+
+    # -- state ---------------------------------------------------------------------
+    def reset(self):
+        _check(lib().fdc_reset(self._h))
+
+    def set_valid_len(self, v):
+        a = _i32(v)
+        assert a.size == self.B * self.F
+        _check(lib().fdc_set_valid_len(self._h, _p(a)))
+
+    def get_valid_len(self) -> np.ndarray:
+        a = np.zeros(self.B * self.F, dtype=np.int32)
+        _check(lib().fdc_get_valid_len(self._h, _p(a)))
+        return a.reshape(self.B, self.F)
+
+    def kv_append(self, layer: int, k_new, v_new, row_scene, row_pos):
+        torch = self.torch
+        k = self._dev_bf16(k_new)
+        v = self._dev_bf16(v_new)
+        rs = torch.as_tensor(np.asarray(row_scene, dtype=np.int32)).to(self.device)
+        rp = torch.as_tensor(np.asarray(row_pos, dtype=np.int32)).to(self.device)
+        n = rs.numel()
+        assert k.numel() == n * self.dims.n_kv_heads * self.dims.head_dim == v.numel()
+        _check(lib().fdc_kv_append(self._h, layer, k.data_ptr(), v.data_ptr(), rs.data_ptr(),
+                                   rp.data_ptr(), n, _stream()))
+        torch.cuda.current_stream().synchronize()      # temporaries die here
+
+    # -- the step -------------------------------------------------------------------
+    def parallel_decode_step(self, branch_field, branch_off, tok_in=None, emb_in=None, T: int = 1,
+                             want_logits=False, want_hidden=False, want_gap=True) -> dict:
+        torch = self.torch
+        bf, bo = _i32(branch_field), _i32(branch_off)
+        assert bf.size == bo.size and bf.size % self.B == 0
+        R = bf.size // self.B
+        M = self.B * R * T
+        d = self.dims
+        dev = self.device
+        tok_t = emb_t = None
+        if tok_in is not None:
+            tok_t = tok_in if isinstance(tok_in, torch.Tensor) else \
+                torch.as_tensor(np.asarray(tok_in, dtype=np.int32).reshape(-1)).to(dev)
+            assert tok_t.numel() == M and tok_t.dtype == torch.int32
+        if emb_in is not None:
+            emb_t = self._dev_bf16(emb_in)
+            assert emb_t.numel() == M * d.d_model
+        out = {"tok": torch.empty(M, dtype=torch.int32, device=dev)}
+        if want_gap:
+            out["gap"] = torch.empty(M, dtype=torch.float32, device=dev)
+        if want_logits:
+            out["logits"] = torch.empty(M, d.vocab, dtype=torch.float32, device=dev)
+        if want_hidden:
+            out["hidden"] = torch.zeros(d.n_layers + 2, M, d.d_model, dtype=torch.float32, device=dev)
+        ptr = lambda k: out[k].data_ptr() if k in out else None
+        _check(lib().fdc_parallel_decode_step(
+            self._h, R, T, _p(bf), _p(bo),
+            tok_t.data_ptr() if tok_t is not None else None,
+            emb_t.data_ptr() if emb_t is not None else None,
+            ptr("tok"), ptr("gap"), ptr("logits"), ptr("hidden"), _stream()))
+        out["_inputs"] = (tok_t, emb_t)            # keep alive until the caller syncs
+        return out
+
+    def masked_attention(self, layer: int, q, branch_field, branch_off, T: int = 1):
+        torch = self.torch
+        bf, bo = _i32(branch_field), _i32(branch_off)
+        R = bf.size // self.B
+        M = self.B * R * T
+        d = self.dims
+        qt = self._dev_bf16(q)
+        assert qt.numel() == M * d.n_q_heads * d.head_dim
+        out = torch.empty(M, d.n_q_heads * d.head_dim, dtype=torch.float32, device=self.device)
+        _check(lib().fdc_masked_attention(self._h, layer, qt.data_ptr(), R, T, _p(bf), _p(bo),
+                                          out.data_ptr(), _stream()))
+        out._fdc_q = qt
+        return out

@@ -1,0 +1,661 @@
+// C ABI of the library: context, buffers, and the orchestration of one
+// parallel decoding step (Sec. 3.3) out of the gfx950 kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "fdc_internal.hpp"
+#include "fdc_launch.hpp"
+
+using namespace fdc;
+
+#define FDC_HIP(call)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail(FDC_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));             \
+    } while (0)
+
+namespace {
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+}  // namespace
+
+struct fdc_ctx {
+    fdc_model_desc m{};
+    int F = 0, P = 0, N = 0, Npad = 0, NB = 0, B = 0, Rmax = 0, Tmax = 0, Mmax = 0;
+    std::vector<int32_t> slot_len, slot_start, level, valid_len;
+    std::vector<uint64_t> anc;
+    std::vector<fdc_layer_weights> lw;
+    std::vector<char> lw_set;
+    const uint16_t* emb = nullptr;
+    const float* gf = nullptr;
+    const uint16_t* lm = nullptr;
+    uint16_t* kc = nullptr;
+    uint16_t* vc = nullptr;
+    size_t kv_layer_elems = 0;
+
+    GemmPlan p_qkv, p_o, p_gu, p_down, p_lm;
+
+    // attention launch shape for the largest step
+    int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1;
+
+    // workspace
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    struct Off {
+        size_t anc, slot_start, slot_tab, inv_freq, meta, x, a_hi, a_lo, o_hi, o_lo, h_hi, h_lo, q,
+            part, logits, attn_o, attn_ml, tok_tmp, end;
+    } off{};
+    size_t meta_ints = 0;
+
+    // pinned staging ring for the per-step tables
+    int32_t* stage[kStageSlots] = {};
+    hipEvent_t stage_ev[kStageSlots] = {};
+    bool stage_used[kStageSlots] = {};
+    int stage_next = 0;
+
+    template <class T>
+    T* at(size_t o) const { return reinterpret_cast<T*>(ws + o); }
+};
+
+namespace {
+
+void plan_attention(fdc_ctx* c) {
+    const int G = c->m.n_q_heads / c->m.n_kv_heads;
+    const int rows = c->Rmax * c->Tmax * G;
+    c->attn_nrt = rows > 32 ? 2 : 1;
+    const int NR = c->attn_nrt * 32;
+    c->attn_rg_max = (rows + NR - 1) / NR;
+    // enough workgroups to cover the chip a few times, at least one 32-key tile
+    // per wavefront
+    const long zr = (long)c->B * c->m.n_kv_heads * c->attn_rg_max;
+    const long want_wgs = 768;
+    long chunks = std::max(1L, want_wgs / zr);
+    long cb = (c->NB + chunks - 1) / chunks;
+    cb = std::max(4L, (cb + 3) / 4 * 4);
+    c->attn_cb = (int)cb;
+    c->attn_chunks = (int)((c->NB + cb - 1) / cb);
+}
+
+size_t carve(fdc_ctx* c) {
+    const fdc_model_desc& m = c->m;
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes);
+        return at;
+    };
+    const int Mp = kMaxRowsDense;
+    const size_t HqD = (size_t)m.n_q_heads * m.head_dim;
+    const size_t Nqkv = (size_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
+    c->off.anc = take(sizeof(uint64_t) * c->F);
+    c->off.slot_start = take(sizeof(int32_t) * c->F);
+    c->off.slot_tab = take(sizeof(uint32_t) * std::max(1, c->Npad - c->P));
+    c->off.inv_freq = take(sizeof(double) * (m.head_dim / 2));
+    c->meta_ints = (size_t)2 * c->B * c->Rmax + (size_t)c->B * c->F;
+    c->off.meta = take(sizeof(int32_t) * c->meta_ints);
+    c->off.x = take(sizeof(float) * Mp * m.d_model);
+    c->off.a_hi = take(2 * (size_t)Mp * m.d_model);
+    c->off.a_lo = take(2 * (size_t)Mp * m.d_model);
+    c->off.o_hi = take(2 * (size_t)Mp * HqD);
+    c->off.o_lo = take(2 * (size_t)Mp * HqD);
+    c->off.h_hi = take(2 * (size_t)Mp * m.d_mlp);
+    c->off.h_lo = take(2 * (size_t)Mp * m.d_mlp);
+    c->off.q = take(2 * (size_t)c->Mmax * HqD);
+    size_t part = 0;
+    part = std::max(part, (size_t)c->p_qkv.S * Mp * Nqkv);
+    part = std::max(part, (size_t)c->p_o.S * Mp * m.d_model);
+    part = std::max(part, (size_t)c->p_down.S * Mp * m.d_model);
+    c->off.part = take(sizeof(float) * part);
+    c->off.logits = take(sizeof(float) * Mp * m.vocab);
+    const size_t zr = (size_t)c->B * m.n_kv_heads * c->attn_rg_max;
+    const size_t NR = (size_t)c->attn_nrt * 32;
+    c->off.attn_o = take(sizeof(float) * zr * c->attn_chunks * NR * m.head_dim);
+    c->off.attn_ml = take(sizeof(float) * zr * c->attn_chunks * NR * 2);
+    c->off.tok_tmp = take(sizeof(int32_t) * c->Mmax);
+    c->off.end = o;
+    return o;
+}
+
+int32_t check_step(const fdc_ctx* c, int R, int T, const int32_t* bf, const int32_t* bo) {
+    if (!bf || !bo) return fail(FDC_EINVAL, "branch_field / branch_off is null");
+    if (R < 1 || R > c->Rmax) return fail(FDC_ECAP, "n_branches %d outside 1..%d", R, c->Rmax);
+    if (T < 1 || T > c->Tmax) return fail(FDC_ECAP, "T %d outside 1..%d", T, c->Tmax);
+    for (int i = 0; i < c->B * R; ++i) {
+        const int f = bf[i];
+        if (f == -1) continue;
+        if (f < 0 || f >= c->F) return fail(FDC_ERANGE, "branch %d: field %d outside 0..%d", i, f, c->F - 1);
+        if (bo[i] < 0 || bo[i] + T > c->slot_len[f])
+            return fail(FDC_ERANGE, "branch %d: offsets %d..%d do not fit slot %d of length %d", i,
+                        bo[i], bo[i] + T - 1, f, c->slot_len[f]);
+    }
+    return FDC_OK;
+}
+
+// copies branch tables + valid_len to the device through the pinned ring
+int32_t upload_meta(fdc_ctx* c, int R, const int32_t* bf, const int32_t* bo, hipStream_t st,
+                    StepMeta* sm, int T) {
+    const int slot = c->stage_next;
+    c->stage_next = (slot + 1) % kStageSlots;
+    if (c->stage_used[slot]) FDC_HIP(hipEventSynchronize(c->stage_ev[slot]));
+    int32_t* h = c->stage[slot];
+    const size_t nbr = (size_t)c->B * R;
+    std::memcpy(h, bf, sizeof(int32_t) * nbr);
+    std::memcpy(h + nbr, bo, sizeof(int32_t) * nbr);
+    std::memcpy(h + 2 * nbr, c->valid_len.data(), sizeof(int32_t) * c->B * c->F);
+    int32_t* d = c->at<int32_t>(c->off.meta);
+    const size_t n = 2 * nbr + (size_t)c->B * c->F;
+    FDC_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * n, hipMemcpyHostToDevice, st));
+    FDC_HIP(hipEventRecord(c->stage_ev[slot], st));
+    c->stage_used[slot] = true;
+    sm->branch_field = d;
+    sm->branch_off = d + nbr;
+    sm->valid_len = d + 2 * nbr;
+    sm->slot_start = c->at<int32_t>(c->off.slot_start);
+    sm->B = c->B;
+    sm->R = R;
+    sm->T = T;
+    sm->F = c->F;
+    return FDC_OK;
+}
+
+void fill_attn(const fdc_ctx* c, int layer, int R, int T, AttnArgs* a) {
+    const fdc_model_desc& m = c->m;
+    const int G = m.n_q_heads / m.n_kv_heads;
+    const int rows = R * T * G;
+    std::memset(a, 0, sizeof(*a));
+    a->kc = c->kc + (size_t)layer * c->kv_layer_elems;
+    a->vc = c->vc + (size_t)layer * c->kv_layer_elems;
+    a->part_o = c->at<float>(c->off.attn_o);
+    a->part_ml = c->at<float>(c->off.attn_ml);
+    a->anc = c->at<uint64_t>(c->off.anc);
+    a->slot_tab = c->at<uint32_t>(c->off.slot_tab);
+    a->Hq = m.n_q_heads;
+    a->Hkv = m.n_kv_heads;
+    a->G = G;
+    a->D = m.head_dim;
+    a->P = c->P;
+    a->NB = c->NB;
+    a->CB = c->attn_cb;
+    a->n_chunks = c->attn_chunks;
+    a->nrt = c->attn_nrt;
+    const int NR = a->nrt * 32;
+    a->n_rg = (rows + NR - 1) / NR;
+    a->scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m.head_dim));
+}
+
+bool aligned(const void* p, size_t a = 16) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+namespace fdc {
+
+GemmPlan plan_gemm(int64_t n_out, int64_t k_in, bool swiglu) {
+    GemmPlan p;
+    p.KT = (int)(k_in / 32);
+    p.n_tiles = (int)((n_out + 15) / 16);
+    p.nt = swiglu ? 2 : 1;
+    p.n_tasks = p.n_tiles / p.nt;
+    const int cap = 8 * 16;                          // k tiles one workgroup keeps in registers
+    int S = 1;
+    if (!swiglu) {
+        const int s_min = (p.KT + cap - 1) / cap;
+        const int s_want = (768 + p.n_tasks - 1) / std::max(1, p.n_tasks);
+        S = std::max(s_min, std::min(s_want, std::max(1, p.KT / 4)));
+        S = std::max(s_min, std::min(S, 16));
+    }
+    p.kt_split = (p.KT + S - 1) / S;
+    p.S = (p.KT + p.kt_split - 1) / p.kt_split;
+    p.nw = p.kt_split >= 32 ? 8 : p.kt_split >= 16 ? 4 : p.kt_split >= 8 ? 2 : 1;
+    const int per = (p.kt_split + p.nw - 1) / p.nw;
+    static const int buckets[] = {2, 4, 6, 8, 10, 12, 14, 16, 20};
+    p.ktw = 0;
+    for (int b : buckets)
+        if (b >= per) {
+            p.ktw = b;
+            break;
+        }
+    const int waves_per_cu = p.ktw <= 8 ? 16 : 8;
+    const int wgs = std::max(1, 256 * std::max(1, waves_per_cu / p.nw) / p.S);
+    p.grid = p.S * std::min(p.n_tasks, wgs);
+    return p;
+}
+
+}  // namespace fdc
+
+extern "C" {
+
+size_t fdc_packed_weight_bytes(int64_t n_out, int64_t k_in) {
+    if (n_out <= 0 || k_in <= 0) return 0;
+    return (size_t)((n_out + 15) / 16 * 16) * (size_t)k_in * 2;
+}
+
+int32_t fdc_pack_weight(const void* src, void* dst, int64_t n_out, int64_t k_in, int32_t mode,
+                        void* stream) {
+    if (!src || !dst) return fail(FDC_EINVAL, "null pointer argument");
+    if (n_out <= 0 || k_in <= 0 || k_in % 32)
+        return fail(FDC_EINVAL, "n_out (%lld) must be positive and k_in (%lld) a multiple of 32",
+                    (long long)n_out, (long long)k_in);
+    if (mode != FDC_PACK_PLAIN && mode != FDC_PACK_GATE_UP) return fail(FDC_EINVAL, "unknown pack mode %d", mode);
+    if (mode == FDC_PACK_GATE_UP && n_out % 32) return fail(FDC_EINVAL, "gate/up packing needs n_out %% 32 == 0");
+    if (!aligned(src) || !aligned(dst)) return fail(FDC_EINVAL, "pointers must be 16-byte aligned");
+    launch_pack_weight((const uint16_t*)src, (uint16_t*)dst, n_out, k_in, mode, (hipStream_t)stream);
+    FDC_HIP(hipGetLastError());
+    return FDC_OK;
+}
+
+int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t* slot_len,
+                   int32_t n_edges, const int32_t* edge_src, const int32_t* edge_dst,
+                   int32_t prefix_len, int32_t n_scenes, int32_t max_branches, int32_t max_tokens,
+                   fdc_ctx** out) {
+    if (!model || !out) return fail(FDC_EINVAL, "null pointer argument");
+    *out = nullptr;
+    const fdc_model_desc& m = *model;
+    if (m.n_layers < 1 || m.d_model < 32 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.d_mlp < 32 ||
+        m.vocab < 2 || !(m.rope_base > 1.0f) || !(m.norm_eps >= 0.0f))
+        return fail(FDC_EINVAL, "bad model description");
+    if (m.head_dim != 64 && m.head_dim != 128) return fail(FDC_ECAP, "head_dim %d: only 64 and 128 are built", m.head_dim);
+    if (m.n_q_heads % m.n_kv_heads) return fail(FDC_EINVAL, "n_kv_heads must divide n_q_heads");
+    if (m.d_model % 32 || m.d_mlp % 32 || m.vocab % 4)
+        return fail(FDC_ECAP, "d_model and d_mlp must be multiples of 32, vocab of 4");
+    if (n_fields > kMaxFields) return fail(FDC_ECAP, "n_fields %d above %d", n_fields, kMaxFields);
+    if (n_scenes < 1 || max_branches < 1 || max_tokens < 1) return fail(FDC_EINVAL, "bad batch shape");
+    if (m.d_model > 8 * 20 * 32) return fail(FDC_ECAP, "d_model above %d", 8 * 20 * 32);
+
+    fdc_ctx* c = new (std::nothrow) fdc_ctx;
+    if (!c) return fail(FDC_EINVAL, "out of host memory");
+    c->m = m;
+    c->F = n_fields > 0 ? n_fields : 0;
+    c->anc.resize(std::max(1, n_fields));
+    c->slot_start.resize(std::max(1, n_fields));
+    c->level.resize(std::max(1, n_fields));
+    int32_t N = 0;
+    int32_t rc = build_plan(n_fields, slot_len, n_edges, edge_src, edge_dst, prefix_len,
+                            c->anc.data(), c->slot_start.data(), c->level.data(), &N);
+    if (rc != FDC_OK) {
+        delete c;
+        return rc;
+    }
+    c->slot_len.assign(slot_len, slot_len + n_fields);
+    c->P = prefix_len;
+    c->N = N;
+    c->Npad = (N + 31) / 32 * 32;
+    c->NB = c->Npad / 32;
+    c->B = n_scenes;
+    c->Rmax = max_branches;
+    c->Tmax = max_tokens;
+    c->Mmax = n_scenes * max_branches * max_tokens;
+    c->valid_len.assign((size_t)n_scenes * n_fields, 0);
+    c->lw.resize(m.n_layers);
+    c->lw_set.assign(m.n_layers, 0);
+    c->kv_layer_elems = (size_t)n_scenes * m.n_kv_heads * c->Npad * m.head_dim;
+    const int64_t HqD = (int64_t)m.n_q_heads * m.head_dim;
+    c->p_qkv = plan_gemm(HqD + 2 * (int64_t)m.n_kv_heads * m.head_dim, m.d_model, false);
+    c->p_o = plan_gemm(m.d_model, HqD, false);
+    c->p_gu = plan_gemm(2 * (int64_t)m.d_mlp, m.d_model, true);
+    c->p_down = plan_gemm(m.d_model, m.d_mlp, false);
+    c->p_lm = plan_gemm(m.vocab, m.d_model, false);
+    c->p_lm.S = 1;     // logits are written in place: one split
+    c->p_lm.kt_split = c->p_lm.KT;
+    {
+        GemmPlan& p = c->p_lm;
+        p.nw = 8;
+        const int per = (p.kt_split + p.nw - 1) / p.nw;
+        p.ktw = per <= 2 ? 2 : per <= 4 ? 4 : per <= 6 ? 6 : per <= 8 ? 8 : per <= 10 ? 10 : per <= 12 ? 12
+              : per <= 14 ? 14 : per <= 16 ? 16 : 20;
+        p.grid = std::min(p.n_tasks, 256 * (p.ktw <= 8 ? 2 : 1));
+    }
+    for (const GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_down, &c->p_lm})
+        if (p->ktw == 0) {
+            delete c;
+            return fail(FDC_ECAP, "projection with K = %d does not fit the streaming kernel", p->KT * 32);
+        }
+    plan_attention(c);
+    carve(c);
+    const size_t stage_bytes = sizeof(int32_t) * c->meta_ints;
+    for (int i = 0; i < kStageSlots; ++i) {
+        if (hipHostMalloc((void**)&c->stage[i], stage_bytes, hipHostMallocDefault) != hipSuccess ||
+            hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming) != hipSuccess) {
+            fdc_destroy(c);
+            return fail(FDC_EHIP, "could not allocate pinned staging memory");
+        }
+    }
+    *out = c;
+    return FDC_OK;
+}
+
+void fdc_destroy(fdc_ctx* c) {
+    if (!c) return;
+    for (int i = 0; i < kStageSlots; ++i) {
+        if (c->stage_ev[i]) {
+            (void)hipEventSynchronize(c->stage_ev[i]);
+            (void)hipEventDestroy(c->stage_ev[i]);
+        }
+        if (c->stage[i]) (void)hipHostFree(c->stage[i]);
+    }
+    delete c;
+}
+
+size_t fdc_kv_cache_bytes(const fdc_ctx* c) {
+    return c ? sizeof(uint16_t) * c->kv_layer_elems * c->m.n_layers : 0;
+}
+
+size_t fdc_workspace_bytes(const fdc_ctx* c) { return c ? c->off.end : 0; }
+
+int32_t fdc_set_kv_cache(fdc_ctx* c, void* k, void* v) {
+    if (!c || !k || !v) return fail(FDC_EINVAL, "null pointer argument");
+    if (!aligned(k, 256) || !aligned(v, 256)) return fail(FDC_EINVAL, "cache pointers must be 256-byte aligned");
+    c->kc = (uint16_t*)k;
+    c->vc = (uint16_t*)v;
+    return FDC_OK;
+}
+
+int32_t fdc_set_workspace(fdc_ctx* c, void* ws, size_t bytes, void* stream) {
+    if (!c || !ws) return fail(FDC_EINVAL, "null pointer argument");
+    if (!aligned(ws, 256)) return fail(FDC_EINVAL, "workspace must be 256-byte aligned");
+    if (bytes < c->off.end) return fail(FDC_EINVAL, "workspace of %zu bytes, %zu needed", bytes, c->off.end);
+    hipStream_t st = (hipStream_t)stream;
+    c->ws = (char*)ws;
+    c->ws_bytes = bytes;
+    // template tables (pageable host memory: the copies complete before return)
+    std::vector<uint32_t> tab(std::max(1, c->Npad - c->P), 0xffffffffu);
+    for (int f = 0; f < c->F; ++f)
+        for (int t = 0; t < c->slot_len[f]; ++t)
+            tab[c->slot_start[f] - c->P + t] = (uint32_t)f | ((uint32_t)t << 8);
+    std::vector<double> inv(c->m.head_dim / 2);
+    for (int i = 0; i < c->m.head_dim / 2; ++i)
+        inv[i] = std::pow((double)c->m.rope_base, -2.0 * i / c->m.head_dim);
+    FDC_HIP(hipMemsetAsync(ws, 0, c->off.end, st));
+    FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.anc), c->anc.data(), sizeof(uint64_t) * c->F, hipMemcpyHostToDevice, st));
+    FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.slot_start), c->slot_start.data(), sizeof(int32_t) * c->F, hipMemcpyHostToDevice, st));
+    FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.slot_tab), tab.data(), sizeof(uint32_t) * tab.size(), hipMemcpyHostToDevice, st));
+    FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.inv_freq), inv.data(), sizeof(double) * inv.size(), hipMemcpyHostToDevice, st));
+    FDC_HIP(hipStreamSynchronize(st));
+    return FDC_OK;
+}
+
+int32_t fdc_set_layer_weights(fdc_ctx* c, int32_t layer, const fdc_layer_weights* w) {
+    if (!c || !w) return fail(FDC_EINVAL, "null pointer argument");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(FDC_ERANGE, "layer %d outside 0..%d", layer, c->m.n_layers - 1);
+    if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wgu || !w->wd) return fail(FDC_EINVAL, "null weight pointer");
+    for (const void* p : {(const void*)w->g1, w->wqkv, w->wo, (const void*)w->g2, w->wgu, w->wd})
+        if (!aligned(p)) return fail(FDC_EINVAL, "weight pointers must be 16-byte aligned");
+    c->lw[layer] = *w;
+    c->lw_set[layer] = 1;
+    return FDC_OK;
+}
+
+int32_t fdc_set_head_weights(fdc_ctx* c, const void* emb, const float* gf, const void* lm) {
+    if (!c || !emb || !gf || !lm) return fail(FDC_EINVAL, "null pointer argument");
+    if (!aligned(emb) || !aligned(gf) || !aligned(lm)) return fail(FDC_EINVAL, "weight pointers must be 16-byte aligned");
+    c->emb = (const uint16_t*)emb;
+    c->gf = gf;
+    c->lm = (const uint16_t*)lm;
+    return FDC_OK;
+}
+
+int32_t fdc_reset(fdc_ctx* c) {
+    if (!c) return fail(FDC_EINVAL, "null context");
+    std::fill(c->valid_len.begin(), c->valid_len.end(), 0);
+    return FDC_OK;
+}
+
+int32_t fdc_set_valid_len(fdc_ctx* c, const int32_t* v) {
+    if (!c || !v) return fail(FDC_EINVAL, "null pointer argument");
+    for (int b = 0; b < c->B; ++b)
+        for (int g = 0; g < c->F; ++g)
+            if (v[b * c->F + g] < 0 || v[b * c->F + g] > c->slot_len[g])
+                return fail(FDC_ERANGE, "valid_len[%d][%d] = %d outside 0..%d", b, g, v[b * c->F + g], c->slot_len[g]);
+    c->valid_len.assign(v, v + (size_t)c->B * c->F);
+    return FDC_OK;
+}
+
+int32_t fdc_get_valid_len(const fdc_ctx* c, int32_t* v) {
+    if (!c || !v) return fail(FDC_EINVAL, "null pointer argument");
+    std::memcpy(v, c->valid_len.data(), sizeof(int32_t) * c->valid_len.size());
+    return FDC_OK;
+}
+
+int32_t fdc_kv_append(fdc_ctx* c, int32_t layer, const void* k_new, const void* v_new,
+                      const int32_t* row_scene, const int32_t* row_pos, int32_t n_rows, void* stream) {
+    if (!c) return fail(FDC_EINVAL, "null context");
+    if (!c->kc || !c->vc) return fail(FDC_ESTATE, "KV cache not set");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(FDC_ERANGE, "layer %d outside 0..%d", layer, c->m.n_layers - 1);
+    if (n_rows < 0) return fail(FDC_EINVAL, "n_rows < 0");
+    if (n_rows == 0) return FDC_OK;
+    if (!k_new || !v_new || !row_scene || !row_pos) return fail(FDC_EINVAL, "null pointer argument");
+    launch_kv_scatter((const uint16_t*)k_new, (const uint16_t*)v_new, row_scene, row_pos, n_rows,
+                      c->kc + (size_t)layer * c->kv_layer_elems, c->vc + (size_t)layer * c->kv_layer_elems,
+                      c->B, c->m.n_kv_heads, c->m.head_dim, c->NB, c->N, (hipStream_t)stream);
+    FDC_HIP(hipGetLastError());
+    return FDC_OK;
+}
+
+int32_t fdc_masked_attention(fdc_ctx* c, int32_t layer, const void* q, int32_t R, int32_t T,
+                             const int32_t* bf, const int32_t* bo, float* out, void* stream) {
+    if (!c || !q || !out) return fail(FDC_EINVAL, "null pointer argument");
+    if (!c->kc || !c->vc || !c->ws) return fail(FDC_ESTATE, "KV cache or workspace not set");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(FDC_ERANGE, "layer %d outside 0..%d", layer, c->m.n_layers - 1);
+    int32_t rc = check_step(c, R, T, bf, bo);
+    if (rc != FDC_OK) return rc;
+    for (int i = 0; i < c->B * R; ++i)
+        if (bf[i] >= 0 && c->valid_len[(size_t)(i / R) * c->F + bf[i]] < bo[i] + T)
+            return fail(FDC_ERANGE, "branch %d: valid_len does not cover the rows' own tokens", i);
+    if (!aligned(q) || !aligned(out)) return fail(FDC_EINVAL, "pointers must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    StepMeta sm;
+    rc = upload_meta(c, R, bf, bo, st, &sm, T);
+    if (rc != FDC_OK) return rc;
+    AttnArgs a;
+    fill_attn(c, layer, R, T, &a);
+    a.q = (const uint16_t*)q;
+    a.out_f32 = out;
+    launch_attention(a, sm, st);
+    FDC_HIP(hipGetLastError());
+    return FDC_OK;
+}
+
+int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t* bf,
+                                 const int32_t* bo, const int32_t* tok_in, const void* emb_in,
+                                 int32_t* tok_out, float* gap_out, float* logits_out,
+                                 float* hidden_out, void* stream) {
+    if (!c) return fail(FDC_EINVAL, "null context");
+    if (!c->kc || !c->vc || !c->ws || !c->emb || !c->gf || !c->lm) return fail(FDC_ESTATE, "cache, workspace or head weights not set");
+    for (int l = 0; l < c->m.n_layers; ++l)
+        if (!c->lw_set[l]) return fail(FDC_ESTATE, "weights of layer %d not set", l);
+    if (!tok_out) return fail(FDC_EINVAL, "tok_out is null");
+    if ((tok_in == nullptr) == (emb_in == nullptr)) return fail(FDC_EINVAL, "give exactly one of tok_in and emb_in");
+    int32_t rc = check_step(c, R, T, bf, bo);
+    if (rc != FDC_OK) return rc;
+    const fdc_model_desc& m = c->m;
+    const int M = c->B * R * T;
+    if (M > kMaxRowsDense) return fail(FDC_ECAP, "%d rows in one step; the projections take at most %d", M, kMaxRowsDense);
+    if ((emb_in && !aligned(emb_in)) || (logits_out && !aligned(logits_out)) || (hidden_out && !aligned(hidden_out)))
+        return fail(FDC_EINVAL, "pointers must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+
+    // append-then-attend: the step's own tokens count as written
+    std::vector<int32_t> saved = c->valid_len;
+    for (int i = 0; i < c->B * R; ++i)
+        if (bf[i] >= 0) {
+            int32_t& v = c->valid_len[(size_t)(i / R) * c->F + bf[i]];
+            v = std::max(v, bo[i] + T);
+        }
+    StepMeta sm;
+    rc = upload_meta(c, R, bf, bo, st, &sm, T);
+    if (rc != FDC_OK) {
+        c->valid_len = saved;
+        return rc;
+    }
+
+    const int d = m.d_model, HqD = m.n_q_heads * m.head_dim;
+    const int Nqkv = HqD + 2 * m.n_kv_heads * m.head_dim;
+    float* x = c->at<float>(c->off.x);
+    float* part = c->at<float>(c->off.part);
+    uint16_t *a_hi = c->at<uint16_t>(c->off.a_hi), *a_lo = c->at<uint16_t>(c->off.a_lo);
+    uint16_t *o_hi = c->at<uint16_t>(c->off.o_hi), *o_lo = c->at<uint16_t>(c->off.o_lo);
+    uint16_t *h_hi = c->at<uint16_t>(c->off.h_hi), *h_lo = c->at<uint16_t>(c->off.h_lo);
+    uint16_t* q = c->at<uint16_t>(c->off.q);
+    float* logits = logits_out ? logits_out : c->at<float>(c->off.logits);
+    const size_t hstride = (size_t)M * d;
+
+    NormArgs na{};
+    na.x = x;
+    na.eps = m.norm_eps;
+    na.a_hi = a_hi;
+    na.a_lo = a_lo;
+    na.M = M;
+    na.d = d;
+    na.vocab = m.vocab;
+
+    for (int l = 0; l < m.n_layers; ++l) {
+        const fdc_layer_weights& w = c->lw[l];
+        // residual (embedding, or + MLP output of the previous layer) and attention norm
+        NormArgs n1 = na;
+        if (l == 0) {
+            n1.tok = tok_in;
+            n1.emb = c->emb;
+            n1.emb_rows = (const uint16_t*)emb_in;
+        } else {
+            n1.part = part;
+            n1.S = c->p_down.S;
+        }
+        n1.gain = w.g1;
+        n1.hidden_x = hidden_out ? hidden_out + (size_t)l * hstride : nullptr;
+        launch_resid_norm(n1, sm, st);
+
+        GemmArgs g{};
+        g.w = (const uint16_t*)w.wqkv;
+        g.act_hi = a_hi;
+        g.act_lo = a_lo;
+        g.out = part;
+        g.M = M;
+        g.N = Nqkv;
+        g.n_valid = Nqkv;
+        launch_gemm(c->p_qkv, EPI_PARTIAL, g, st);
+
+        RopeArgs ra{};
+        ra.part = part;
+        ra.S = c->p_qkv.S;
+        ra.q = q;
+        ra.kc = c->kc + (size_t)l * c->kv_layer_elems;
+        ra.vc = c->vc + (size_t)l * c->kv_layer_elems;
+        ra.inv_freq = c->at<double>(c->off.inv_freq);
+        ra.M = M;
+        ra.Hq = m.n_q_heads;
+        ra.Hkv = m.n_kv_heads;
+        ra.D = m.head_dim;
+        ra.NB = c->NB;
+        launch_rope_append(ra, sm, st);
+
+        AttnArgs aa;
+        fill_attn(c, l, R, T, &aa);
+        aa.q = q;
+        aa.out_hi = o_hi;
+        aa.out_lo = o_lo;
+        launch_attention(aa, sm, st);
+
+        g.w = (const uint16_t*)w.wo;
+        g.act_hi = o_hi;
+        g.act_lo = o_lo;
+        g.N = d;
+        g.n_valid = d;
+        launch_gemm(c->p_o, EPI_PARTIAL, g, st);
+
+        NormArgs n2 = na;
+        n2.part = part;
+        n2.S = c->p_o.S;
+        n2.gain = w.g2;
+        launch_resid_norm(n2, sm, st);
+
+        GemmArgs gu{};
+        gu.w = (const uint16_t*)w.wgu;
+        gu.act_hi = a_hi;
+        gu.act_lo = a_lo;
+        gu.out_hi = h_hi;
+        gu.out_lo = h_lo;
+        gu.out_KT = m.d_mlp / 32;
+        gu.M = M;
+        launch_gemm(c->p_gu, EPI_SWIGLU, gu, st);
+
+        g.w = (const uint16_t*)w.wd;
+        g.act_hi = h_hi;
+        g.act_lo = h_lo;
+        g.N = d;
+        g.n_valid = d;
+        launch_gemm(c->p_down, EPI_PARTIAL, g, st);
+    }
+    NormArgs nf = na;
+    nf.part = part;
+    nf.S = c->p_down.S;
+    nf.gain = c->gf;
+    nf.hidden_x = hidden_out ? hidden_out + (size_t)m.n_layers * hstride : nullptr;
+    nf.hidden_n = hidden_out ? hidden_out + (size_t)(m.n_layers + 1) * hstride : nullptr;
+    launch_resid_norm(nf, sm, st);
+
+    GemmArgs gl{};
+    gl.w = c->lm;
+    gl.act_hi = a_hi;
+    gl.act_lo = a_lo;
+    gl.out = logits;
+    gl.M = M;
+    gl.N = m.vocab;
+    gl.n_valid = m.vocab;
+    launch_gemm(c->p_lm, EPI_PARTIAL, gl, st);
+    launch_argmax(logits, M, m.vocab, m.vocab, tok_out, gap_out, sm.branch_field, T, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        c->valid_len = saved;
+        return fail(FDC_EHIP, "kernel launch failed: %s", hipGetErrorString(e));
+    }
+    return FDC_OK;
+}
+
+int32_t fdc_argmax(const float* logits, int32_t M, int32_t V, int64_t ld, int32_t* idx_out,
+                   float* gap, void* stream) {
+    if (!logits || !idx_out) return fail(FDC_EINVAL, "null pointer argument");
+    if (M < 0 || V < 1 || ld < V) return fail(FDC_EINVAL, "bad shape M=%d V=%d ld=%lld", M, V, (long long)ld);
+    launch_argmax(logits, M, V, ld, idx_out, gap, nullptr, 1, (hipStream_t)stream);
+    FDC_HIP(hipGetLastError());
+    return FDC_OK;
+}
+
+size_t fdc_linear_scratch_bytes(int32_t M, int64_t n_out, int64_t k_in) {
+    if (M < 1 || M > kMaxRowsDense || n_out < 16 || k_in < 32) return 0;
+    const GemmPlan p = plan_gemm(n_out, k_in, false);
+    return align_up(2 * (size_t)kMaxRowsDense * k_in) * 2 + align_up(sizeof(float) * p.S * M * n_out);
+}
+
+int32_t fdc_linear(const float* x, const void* w, float* y, int32_t M, int64_t n_out, int64_t k_in,
+                   void* scratch, void* stream) {
+    if (!x || !w || !y || !scratch) return fail(FDC_EINVAL, "null pointer argument");
+    if (M < 1 || M > kMaxRowsDense) return fail(FDC_ECAP, "M = %d outside 1..%d", M, kMaxRowsDense);
+    if (n_out <= 0 || k_in <= 0 || n_out % 4 || k_in % 32) return fail(FDC_EINVAL, "n_out must be a multiple of 4, k_in of 32");
+    if (!aligned(w) || !aligned(y) || !aligned(scratch, 256)) return fail(FDC_EINVAL, "misaligned pointer");
+    const GemmPlan p = plan_gemm(n_out, k_in, false);
+    if (p.ktw == 0) return fail(FDC_ECAP, "k_in = %lld does not fit the streaming kernel", (long long)k_in);
+    hipStream_t st = (hipStream_t)stream;
+    char* s = (char*)scratch;
+    const size_t fb = align_up(2 * (size_t)kMaxRowsDense * k_in);
+    uint16_t *hi = (uint16_t*)s, *lo = (uint16_t*)(s + fb);
+    float* part = (float*)(s + 2 * fb);
+    launch_to_frag(x, hi, lo, M, (int)k_in, st);
+    GemmArgs g{};
+    g.w = (const uint16_t*)w;
+    g.act_hi = hi;
+    g.act_lo = lo;
+    g.out = p.S == 1 ? y : part;
+    g.M = M;
+    g.N = (int)n_out;
+    g.n_valid = (int)n_out;
+    launch_gemm(p, EPI_PARTIAL, g, st);
+    if (p.S > 1) launch_sum_partials(part, y, p.S, M, n_out, st);
+    FDC_HIP(hipGetLastError());
+    return FDC_OK;
+}
+
+}  // extern "C"

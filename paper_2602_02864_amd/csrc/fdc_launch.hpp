@@ -1,0 +1,94 @@
+// Host-callable launchers of the gfx950 kernels.  Every launcher only enqueues
+// work on `st`; none allocates or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+#include "fdc_internal.hpp"
+
+namespace fdc {
+
+// ---- projections (gemm_skinny.hip) -----------------------------------------
+enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
+
+struct GemmArgs {
+    const uint16_t* w;        // packed weights
+    const uint16_t* act_hi;   // activation fragments, bf16 head
+    const uint16_t* act_lo;   // bf16 tail, or nullptr
+    float* out;               // EPI_PARTIAL: [S][M][N] fp32
+    uint16_t* out_hi;         // EPI_SWIGLU: fragments of silu(g)*u for the next projection
+    uint16_t* out_lo;
+    int M;                    // valid rows (<= 16)
+    int N;                    // row stride of `out`
+    int n_valid;              // output features actually stored (multiple of 4)
+    int out_KT;               // EPI_SWIGLU: k tiles of the consumer (= d_mlp / 32)
+};
+void launch_gemm(const GemmPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
+void launch_pack_weight(const uint16_t* src, uint16_t* dst, int64_t n_out, int64_t k_in, int mode,
+                        hipStream_t st);
+// x fp32 [M][K] -> hi/lo fragments (no normalisation); y = sum of S partials
+void launch_to_frag(const float* x, uint16_t* hi, uint16_t* lo, int M, int K, hipStream_t st);
+void launch_sum_partials(const float* part, float* y, int S, int M, int64_t N, hipStream_t st);
+
+// ---- row operations (rowops.hip) ---------------------------------------------
+struct StepMeta {             // device copies of the step's small tables
+    const int32_t* branch_field;   // [B*R]
+    const int32_t* branch_off;     // [B*R]
+    const int32_t* valid_len;      // [B*F]
+    const int32_t* slot_start;     // [F]
+    int B, R, T, F;
+};
+
+struct NormArgs {
+    float* x;                 // residual stream [M][d], updated in place
+    const float* part;        // partial sums to add, [S][M][d], or nullptr
+    int S;
+    const int32_t* tok;       // first layer: token ids [M] ...
+    const uint16_t* emb;      // ... gathered from this [V][d] bf16 table
+    const uint16_t* emb_rows; // or input rows [M][d] bf16
+    const float* gain;
+    float eps;
+    uint16_t* a_hi;           // normalised row, fragments for the next projection
+    uint16_t* a_lo;
+    float* hidden_x;          // optional copy of the updated residual [M][d]
+    float* hidden_n;          // optional copy of the normalised row [M][d]
+    int M, d, vocab;
+};
+void launch_resid_norm(const NormArgs& a, const StepMeta& sm, hipStream_t st);
+
+struct RopeArgs {
+    const float* part;        // QKV partials [S][M][Nqkv]
+    int S;
+    uint16_t* q;              // bf16 [M][Hq][D] rotated queries
+    uint16_t* kc;             // layer base of the K cache
+    uint16_t* vc;
+    const double* inv_freq;   // [D/2]
+    int M, Hq, Hkv, D, NB;    // NB = 32-key tiles per (scene, kv head)
+};
+void launch_rope_append(const RopeArgs& a, const StepMeta& sm, hipStream_t st);
+
+void launch_kv_scatter(const uint16_t* k_new, const uint16_t* v_new, const int32_t* row_scene,
+                       const int32_t* row_pos, int n_rows, uint16_t* kc, uint16_t* vc, int B,
+                       int Hkv, int D, int NB, int N, hipStream_t st);
+
+void launch_argmax(const float* logits, int M, int V, int64_t ld, int32_t* idx, float* gap,
+                   const int32_t* branch_field, int T, hipStream_t st);
+
+// ---- attention (attention.hip) -------------------------------------------------
+struct AttnArgs {
+    const uint16_t* q;        // bf16 [M][Hq][D]
+    const uint16_t* kc;       // layer base
+    const uint16_t* vc;
+    float* part_o;            // [z*n_rg][n_chunks][NR*D]
+    float* part_ml;           // [z*n_rg][n_chunks][NR][2]
+    const uint64_t* anc;      // [F]
+    const uint32_t* slot_tab; // [Npad - P]: field | offset << 8, ~0 for tile padding
+    float* out_f32;           // merge output: fp32 [M][Hq*D] ...
+    uint16_t* out_hi;         // ... or fragments with K = Hq*D
+    uint16_t* out_lo;
+    int Hq, Hkv, G, D, P, NB, CB, n_chunks, n_rg, nrt;
+    float scale_log2;         // log2(e) / sqrt(D)
+};
+void launch_attention(const AttnArgs& a, const StepMeta& sm, hipStream_t st);
+
+}  // namespace fdc

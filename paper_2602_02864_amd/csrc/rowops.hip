@@ -1,0 +1,215 @@
+// Per-row kernels of the decode step: residual add + RMSNorm (also the
+// embedding gather), rotary embedding + KV append at the row's fixed position
+// id, bulk KV scatter, and per-row greedy argmax.  All are bandwidth-trivial;
+// each consumes the split-K partials of the projection before it so that no
+// separate reduction pass exists.
+#include "kernels_common.hpp"
+#include "fdc_launch.hpp"
+
+namespace fdc {
+
+namespace {
+
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    const int wave = threadIdx.x >> 6, nwv = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) sh[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int w = 0; w < nwv; ++w) t += sh[w];
+    __syncthreads();
+    return t;
+}
+
+// One workgroup per row.  x <- (embedding | x + sum of partials); a <- rmsnorm(x) * gain.
+__global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a, StepMeta sm) {
+    __shared__ float sh[4];
+    extern __shared__ float row[];                         // [d]
+    const int m = blockIdx.x;
+    const bool active = sm.branch_field == nullptr || sm.branch_field[m / sm.T] >= 0;
+    float ss = 0.f;
+    for (int k = threadIdx.x; k < a.d; k += blockDim.x) {
+        float v = 0.f;
+        if (active) {
+            if (a.tok) {
+                int t = a.tok[m];
+                t = t < 0 ? 0 : (t >= a.vocab ? a.vocab - 1 : t);
+                v = bf2f(a.emb[(size_t)t * a.d + k]);
+            } else if (a.emb_rows) {
+                v = bf2f(a.emb_rows[(size_t)m * a.d + k]);
+            } else {
+                v = a.x[(size_t)m * a.d + k];
+                for (int s = 0; s < a.S; ++s) v += a.part[((size_t)s * a.M + m) * a.d + k];
+            }
+        }
+        row[k] = v;
+        ss += v * v;
+        a.x[(size_t)m * a.d + k] = v;
+        if (a.hidden_x) a.hidden_x[(size_t)m * a.d + k] = v;
+    }
+    const float tot = block_sum(ss, sh);
+    const float rstd = rsqrtf(tot / (float)a.d + a.eps);
+    const int KT = a.d >> 5;
+    for (int k = threadIdx.x; k < a.d; k += blockDim.x) {
+        const float n = row[k] * rstd * a.gain[k];
+        uint16_t hi, lo;
+        split_bf16(n, hi, lo);
+        const size_t o = act_frag_index(m, k, KT);
+        a.a_hi[o] = hi;
+        a.a_lo[o] = lo;
+        if (a.hidden_n) a.hidden_n[(size_t)m * a.d + k] = n;
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void cache_store(uint16_t* kc, uint16_t* vc, int scene, int kvh, int Hkv,
+                                            int NB, int pos, int d, bool is_k, uint16_t val) {
+    const size_t tile = ((size_t)scene * Hkv + kvh) * NB + (pos >> 5);
+    if (is_k) kc[tile * (32 * D) + k_tile_index<D>(pos & 31, d)] = val;
+    else vc[tile * (32 * D) + v_tile_index<D>(pos & 31, d)] = val;
+}
+
+// One workgroup per row: sum the QKV partials, rotate q and k by the row's
+// position id (slot_start[field] + offset: fixed by the template, Sec. 3.3),
+// store q (bf16) and append k, v to the cache at index = position id.
+template <int D>
+__global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta sm) {
+    const int m = blockIdx.x;
+    const int br = m / sm.T, t = m % sm.T;
+    const int f = sm.branch_field[br];
+    if (f < 0) return;
+    const int scene = br / sm.R;
+    const int pos = sm.slot_start[f] + sm.branch_off[br] + t;
+    const int Nqkv = (a.Hq + 2 * a.Hkv) * D;
+    const int half = D / 2;
+    const int n_pairs = (a.Hq + a.Hkv) * half;
+    for (int p = threadIdx.x; p < n_pairs; p += blockDim.x) {
+        const int hd = p / half, i = p % half;
+        float x1 = 0.f, x2 = 0.f;
+        for (int s = 0; s < a.S; ++s) {
+            const float* r = a.part + ((size_t)s * a.M + m) * Nqkv + hd * D;
+            x1 += r[i];
+            x2 += r[i + half];
+        }
+        double sn, cs;
+        sincos((double)pos * a.inv_freq[i], &sn, &cs);
+        const float c = (float)cs, sf = (float)sn;
+        const float y1 = x1 * c - x2 * sf, y2 = x2 * c + x1 * sf;
+        if (hd < a.Hq) {
+            uint16_t* q = a.q + ((size_t)m * a.Hq + hd) * D;
+            q[i] = f2bf(y1);
+            q[i + half] = f2bf(y2);
+        } else {
+            const int kvh = hd - a.Hq;
+            cache_store<D>(a.kc, a.vc, scene, kvh, a.Hkv, a.NB, pos, i, true, f2bf(y1));
+            cache_store<D>(a.kc, a.vc, scene, kvh, a.Hkv, a.NB, pos, i + half, true, f2bf(y2));
+        }
+    }
+    const int voff = (a.Hq + a.Hkv) * D;
+    for (int e = threadIdx.x; e < a.Hkv * D; e += blockDim.x) {
+        float v = 0.f;
+        for (int s = 0; s < a.S; ++s) v += a.part[((size_t)s * a.M + m) * Nqkv + voff + e];
+        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D, false, f2bf(v));
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_scatter_kernel(const uint16_t* __restrict__ k_new,
+                                                         const uint16_t* __restrict__ v_new,
+                                                         const int32_t* __restrict__ row_scene,
+                                                         const int32_t* __restrict__ row_pos,
+                                                         int n_rows, uint16_t* kc, uint16_t* vc,
+                                                         int B, int Hkv, int NB, int N) {
+    const int r = blockIdx.x;
+    const int scene = row_scene[r], pos = row_pos[r];
+    if (scene < 0 || scene >= B || pos < 0 || pos >= N) return;
+    for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+        const size_t src = (size_t)r * Hkv * D + e;
+        cache_store<D>(kc, vc, scene, e / D, Hkv, NB, pos, e % D, true, k_new[src]);
+        cache_store<D>(kc, vc, scene, e / D, Hkv, NB, pos, e % D, false, v_new[src]);
+    }
+}
+
+struct Top2 {
+    float m1, m2;
+    int i1;
+};
+__device__ __forceinline__ Top2 top2_merge(Top2 a, Top2 b) {
+    if (b.m1 > a.m1 || (b.m1 == a.m1 && b.i1 < a.i1)) {
+        Top2 t = a;
+        a = b;
+        b = t;
+    }
+    a.m2 = fmaxf(a.m2, b.m1);
+    return a;
+}
+
+// One workgroup per row.  Lowest index among equal maxima; gap = best - runner-up.
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int V,
+                                                      int64_t ld, int32_t* idx, float* gap,
+                                                      const int32_t* branch_field, int T) {
+    __shared__ Top2 sh[16];
+    const int m = blockIdx.x;
+    if (branch_field && branch_field[m / T] < 0) {
+        if (threadIdx.x == 0) {
+            idx[m] = -1;
+            if (gap) gap[m] = 0.f;
+        }
+        return;
+    }
+    const float* row = logits + (size_t)m * ld;
+    Top2 t{-INFINITY, -INFINITY, 0x7fffffff};
+    for (int v = threadIdx.x; v < V; v += blockDim.x) {
+        const float x = row[v];
+        if (x > t.m1) {
+            t.m2 = t.m1;
+            t.m1 = x;
+            t.i1 = v;
+        } else if (x > t.m2) {
+            t.m2 = x;
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        Top2 u{__shfl_xor(t.m1, o), __shfl_xor(t.m2, o), __shfl_xor(t.i1, o)};
+        t = top2_merge(t, u);
+    }
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) t = top2_merge(t, sh[w]);
+        idx[m] = t.i1;
+        if (gap) gap[m] = t.m1 - t.m2;
+    }
+}
+
+}  // namespace
+
+void launch_resid_norm(const NormArgs& a, const StepMeta& sm, hipStream_t st) {
+    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.M), dim3(256), a.d * sizeof(float), st, a, sm);
+}
+
+void launch_rope_append(const RopeArgs& a, const StepMeta& sm, hipStream_t st) {
+    if (a.D == 128) hipLaunchKernelGGL(rope_append_kernel<128>, dim3(a.M), dim3(256), 0, st, a, sm);
+    else hipLaunchKernelGGL(rope_append_kernel<64>, dim3(a.M), dim3(256), 0, st, a, sm);
+}
+
+void launch_kv_scatter(const uint16_t* k_new, const uint16_t* v_new, const int32_t* row_scene,
+                       const int32_t* row_pos, int n_rows, uint16_t* kc, uint16_t* vc, int B,
+                       int Hkv, int D, int NB, int N, hipStream_t st) {
+    if (n_rows <= 0) return;
+    if (D == 128)
+        hipLaunchKernelGGL(kv_scatter_kernel<128>, dim3(n_rows), dim3(256), 0, st, k_new, v_new,
+                           row_scene, row_pos, n_rows, kc, vc, B, Hkv, NB, N);
+    else
+        hipLaunchKernelGGL(kv_scatter_kernel<64>, dim3(n_rows), dim3(256), 0, st, k_new, v_new,
+                           row_scene, row_pos, n_rows, kc, vc, B, Hkv, NB, N);
+}
+
+void launch_argmax(const float* logits, int M, int V, int64_t ld, int32_t* idx, float* gap,
+                   const int32_t* branch_field, int T, hipStream_t st) {
+    if (M <= 0) return;
+    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(1024), 0, st, logits, V, ld, idx, gap,
+                       branch_field, T);
+}
+
+}  // namespace fdc

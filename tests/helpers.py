@@ -1,0 +1,118 @@
+"""Shared harness of the GPU parity tests: builds the CPU oracle and the GPU
+context from the same seeded data and compares them.  The oracle and the
+library never see each other; only data (weights, prefix K/V, tokens) is
+shared."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle.fdc_oracle as O
+from synth_inputs import bf16_round, bits_to_f32
+
+HIDDEN_TOL = 2e-3      # max |gpu - ref| / max |ref| per compared tensor (bf16 path vs fp64)
+GAP_MIN = 1e-2         # greedy ids must agree wherever the oracle's top-2 gap exceeds this
+
+
+def rel_err(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
+
+
+def as_f32(a):
+    a = np.asarray(a)
+    return bits_to_f32(a) if a.dtype == np.uint16 else a.astype(np.float32)
+
+
+class Pair:
+    """Oracle decoder + GPU context over the same model, template and prefix."""
+
+    def __init__(self, dims, tpl, weights, n_scenes=1, max_branches=None, max_tokens=1):
+        from paper_2602_02864_amd import Context
+        self.dims, self.tpl, self.w, self.B = dims, tpl, weights, n_scenes
+        F = tpl.n_fields
+        self.Rmax = max_branches or F
+        self.dec = O.OracleDecoder(dims, weights, tpl.prefix_len, tpl.slot_len, tpl.edges, n_scenes)
+        self.ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, n_scenes, self.Rmax, max_tokens)
+        layers = weights["layers"]
+        for l in range(dims.n_layers):
+            self.ctx.set_layer_weights(l, layers(l) if callable(layers) else layers[l])
+        self.ctx.set_head_weights(weights["emb"], weights["gf"], weights["lm"])
+
+    def close(self):
+        self.ctx.close()
+
+    # prefix K/V are data: rounded to bf16 once, handed to both sides
+    def install_prefix_kv(self, scene, K, V):
+        """K, V: [L][Hkv][P][D] float arrays of bf16-representable values."""
+        P = self.tpl.prefix_len
+        self.dec.set_prefix_kv(scene, K, V)
+        for l in range(self.dims.n_layers):
+            self.ctx.kv_append(l, np.ascontiguousarray(np.transpose(K[l], (1, 0, 2)), dtype=np.float32),
+                               np.ascontiguousarray(np.transpose(V[l], (1, 0, 2)), dtype=np.float32),
+                               np.full(P, scene, dtype=np.int32), np.arange(P, dtype=np.int32))
+
+    def prefill_with_oracle(self, scene, prefix_emb):
+        P = self.tpl.prefix_len
+        self.dec.prefill_prefix(scene, prefix_emb)
+        K = bf16_round(self.dec.K[:, scene, :, :P].astype(np.float32))
+        V = bf16_round(self.dec.V[:, scene, :, :P].astype(np.float32))
+        self.install_prefix_kv(scene, K, V)
+
+    def step_both(self, branch_field, branch_off, tok_in, T=1, check=True, tag=""):
+        """Runs one step on both sides with the same (teacher-forced) inputs and
+        compares; returns (oracle output, gpu output as numpy)."""
+        import torch
+        bf = np.asarray(branch_field, dtype=np.int32).reshape(self.B, -1)
+        bo = np.asarray(branch_off, dtype=np.int32).reshape(self.B, -1)
+        R = bf.shape[1]
+        tok = np.asarray(tok_in, dtype=np.int32).reshape(self.B, R, T)
+        ref = self.dec.step(bf, bo, tok_in=tok, T=T)
+        g = self.ctx.parallel_decode_step(bf, bo, tok_in=tok, T=T, want_logits=True, want_hidden=True)
+        torch.cuda.synchronize()
+        got = {k: v.cpu().numpy() for k, v in g.items() if not k.startswith("_")}
+        if check:
+            self.compare(ref, got, tag)
+        return ref, got
+
+    def compare(self, ref, got, tag=""):
+        L = self.dims.n_layers
+        rows = ref["rows"]
+        assert rows.size > 0
+        assert np.array_equal(self.ctx.get_valid_len(), self.dec.valid_len), f"{tag}: valid_len differs"
+        errs = []
+        for l in range(L + 1):
+            errs.append(rel_err(got["hidden"][l][rows], ref["hidden"][l][rows]))
+        errs.append(rel_err(got["hidden"][L + 1][rows], ref["normed"][rows]))
+        e_log = rel_err(got["logits"][rows], ref["logits"][rows])
+        assert np.isfinite(got["logits"][rows]).all(), f"{tag}: non-finite logits"
+        assert max(errs) <= HIDDEN_TOL, f"{tag}: hidden-state error per layer {errs}"
+        assert e_log <= HIDDEN_TOL, f"{tag}: logits error {e_log}"
+        sure = rows[ref["gap"][rows] > GAP_MIN]
+        assert np.array_equal(got["tok"][sure], ref["tok"][sure]), f"{tag}: greedy ids differ"
+        inactive = np.setdiff1d(np.arange(ref["tok"].size), rows)
+        assert (got["tok"][inactive] == -1).all(), f"{tag}: inactive rows must return -1"
+        # the library's own argmax must agree with its own logits exactly
+        assert np.array_equal(got["tok"][rows], np.argmax(got["logits"][rows], axis=1)), f"{tag}: argmax"
+        return max(max(errs), e_log)
+
+
+def run_schedule(pair, content_len, start_token, max_steps=None, tag=""):
+    """Teacher-forced template decoding of scene 0 (B == 1): at every step both
+    sides get the oracle's previous tokens."""
+    tpl = pair.tpl
+    steps = O.schedule(tpl.n_fields, tpl.edges, content_len)
+    if max_steps:
+        steps = steps[:max_steps]
+    R = max(len(s) for s in steps)
+    last = list(start_token)
+    worst = 0.0
+    for si, st in enumerate(steps):
+        bf = [f for f, _ in st] + [-1] * (R - len(st))
+        bo = [o for _, o in st] + [0] * (R - len(st))
+        ti = [last[f] for f, _ in st] + [0] * (R - len(st))
+        ref, got = pair.step_both([bf], [bo], ti, check=False)
+        worst = max(worst, pair.compare(ref, got, f"{tag} step {si}"))
+        for i, (f, _) in enumerate(st):
+            last[f] = int(ref["tok"][i])
+    return worst, len(steps)

