@@ -1,0 +1,353 @@
+#!/usr/bin/env python3
+"""Benchmark of the parallel decoding step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg3]
+
+A step is one pass of the whole hot path (fdc_parallel_decode_step: embedding,
+norms, QKV / O / SwiGLU projections, RoPE + KV append, DAG-masked attention, LM
+head, greedy argmax) over the branches Algorithm 1 has ready.  The default
+workload is the 7B-class configuration (28 layers, d 3584, 28/4 heads x 128,
+MLP 18944, vocab 32000; prefix 3072; 12 fields in a 3-level DAG, 64-token
+slots; batch 1; greedy): the K timed steps are the first K passes of the
+template's schedule (default: the whole schedule, wrapping around if K is
+larger).  Inputs are seeded synthetic tensors already resident in HBM.
+
+Prints ONE JSON line.  `roofline` is the dominant kernel of the step (the
+gate/up projection with fused SwiGLU: weight streaming, HBM-bound) timed with
+HIP events on the launch stream in a second pass over the same steps;
+`cpu_baseline` is the fp64 oracle timed on this host's cores on a bounded
+sample.  `attention` carries the DAG-masked attention micro-benchmark
+(workload 3) with its own HBM roofline fraction.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_model(ctx, dims, seed, torch):
+    """Random-init N(0, 0.02) bf16 weights drawn on the device, gains 1."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    dev = "cuda"
+
+    def w(n, k):
+        return (torch.randn(n, k, generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    ones = torch.ones(dims.d_model, device=dev)
+    HqD = dims.n_q_heads * dims.head_dim
+    for l in range(dims.n_layers):
+        ctx.set_layer_weights(l, {"g1": ones, "g2": ones, "wqkv": w(dims.qkv_out, dims.d_model),
+                                  "wo": w(dims.d_model, HqD), "wgu": w(2 * dims.d_mlp, dims.d_model),
+                                  "wd": w(dims.d_model, dims.d_mlp)})
+    ctx.set_head_weights(w(dims.vocab, dims.d_model), ones, w(dims.vocab, dims.d_model))
+    torch.cuda.synchronize()
+
+
+def weight_bytes(dims):
+    HqD = dims.n_q_heads * dims.head_dim
+    per = {"qkv_proj": dims.qkv_out * dims.d_model, "o_proj": dims.d_model * HqD,
+           "gate_up_swiglu": 2 * dims.d_mlp * dims.d_model, "down_proj": dims.d_model * dims.d_mlp,
+           "lm_head": dims.vocab * dims.d_model}
+    return {k: 2 * v for k, v in per.items()}
+
+
+def run_decode(args, cfg_id):
+    import torch
+    from paper_2602_02864_amd import Context, fdc_schedule
+    from synth_inputs import model_dims, template
+    dims = model_dims(cfg_id)
+    tpl = template(cfg_id)
+    F = tpl.n_fields
+    passes = fdc_schedule(F, tpl.edges, tpl.content_len)
+    R = max(int((bf >= 0).sum()) for bf, _ in passes)
+    passes = [(bf[:R].copy(), bo[:R].copy()) for bf, bo in passes]
+    ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, 1, R, 1)
+    t0 = time.time()
+    build_model(ctx, dims, 2864000 + cfg_id, torch)
+    log(f"[bench] model built in {time.time() - t0:.1f}s, "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
+    # prefix K/V: N(0,1) stand-ins for the prefilled vision/prompt tokens
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    ctx.k_cache.normal_(generator=g)
+    ctx.v_cache.normal_(generator=g)
+
+    K = args.steps if args.steps > 0 else len(passes)
+    W = args.warmup
+    dev = "cuda"
+    # greedy feedback stays on the device: last_tok[f] feeds field f's next row
+    start = torch.tensor(tpl.start_token, dtype=torch.int32, device=dev)
+    idx = [torch.tensor(np.where(bf >= 0, bf, 0), dtype=torch.int64, device=dev) for bf, _ in passes]
+    sel = [torch.tensor(np.nonzero(bf >= 0)[0], dtype=torch.int64, device=dev) for bf, _ in passes]
+    fld = [torch.tensor(bf[bf >= 0], dtype=torch.int64, device=dev) for bf, _ in passes]
+    tok_out = torch.empty(R, dtype=torch.int32, device=dev)
+    from paper_2602_02864_amd import lib
+    from paper_2602_02864_amd.binding import _p, _check, _stream
+    L = lib()
+    state = {"last": start.clone()}
+
+    def one(i):
+        p = i % len(passes)
+        if p == 0:
+            ctx.reset()
+            state["last"] = start.clone()
+        bf, bo = passes[p]
+        tok_in = state["last"][idx[p]].contiguous()
+        _check(L.fdc_parallel_decode_step(ctx._h, R, 1, _p(bf), _p(bo), tok_in.data_ptr(), None,
+                                          tok_out.data_ptr(), None, None, None, _stream()))
+        state["last"].index_copy_(0, fld[p], tok_out.index_select(0, sel[p]))
+        return int((bf >= 0).sum())
+
+    # warm-up: the paper discards the first 10 iterations
+    for i in range(W):
+        one(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tokens = 0
+    t_wall = time.perf_counter()
+    e0.record()
+    for i in range(K):
+        tokens += one(i)
+    e1.record()
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t_wall
+    ms = e0.elapsed_time(e1)
+    ms_per_step = ms / K
+
+    # second pass over the same steps with per-kernel events
+    ctx.profile_enable(True)
+    for i in range(K):
+        one(i)
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    wb = weight_bytes(dims)
+    kernels = {}
+    for name, (kms, n) in prof.items():
+        if n == 0:
+            continue
+        ent = {"avg_us": round(1000.0 * kms / n, 2), "launches": n, "share": round(kms / ms, 4)}
+        if name in wb:
+            ent["GB/s"] = round(wb[name] / (kms / n * 1e-3) / 1e9, 1)
+        kernels[name] = ent
+    dom = "gate_up_swiglu"
+    dom_ms = prof[dom][0] / max(1, prof[dom][1])
+    achieved = wb[dom] / (dom_ms * 1e-3) / 1e9
+    total_w = sum(v * (dims.n_layers if k != "lm_head" else 1) for k, v in wb.items())
+    res = {
+        "metric": "CoT tokens/s in parallel decoding (greedy, batch 1)",
+        "value": round(tokens / (ms * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg{cfg_id}: {dims.n_layers}-layer d={dims.d_model} "
+                               f"{dims.n_q_heads}/{dims.n_kv_heads}x{dims.head_dim} mlp={dims.d_mlp} "
+                               f"vocab={dims.vocab}; prefix {tpl.prefix_len}; {F} fields x "
+                               f"{tpl.slot_len[0]}-token slots; passes {len(passes)}; "
+                               f"tokens {sum(tpl.content_len)}; max ready {R}; batch 1",
+                   "tokens_per_pass": round(tokens / K, 3)},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "bytes_per_launch": wb[dom], "avg_us": round(dom_ms * 1e3, 2)},
+        "step_hbm": {"weight_bytes_per_step": total_w,
+                     "floor_ms_at_peak": round(total_w / HBM_PEAK_GBS / 1e6, 4),
+                     "frac_of_floor": round(total_w / HBM_PEAK_GBS / 1e6 / ms_per_step, 4)},
+        "kernels": kernels,
+        "host_wall_ms_per_step": round(1e3 * t_wall / K, 4),
+    }
+    ctx.close()
+    return res
+
+
+def run_attention(args, rho=None, quick=False):
+    """Workload 3: DAG-masked attention alone. B 16, 32/8 heads x 128, prefix
+    4096, 16 branches x 64-token slots, one query token per branch at offset
+    32, every other slot full.  K/V rotate over several layer-sized buffers
+    larger than the 256 MB Infinity Cache."""
+    import torch
+    from paper_2602_02864_amd import Context
+    from synth_inputs import model_dims, template
+    rho = args.rho if rho is None else rho
+    n_buf = 4
+    dims = model_dims(3, n_layers=n_buf)
+    tpl = template(3, rho=rho, dag_seed=args.dag_seed)
+    B, F, S, P = 16, tpl.n_fields, tpl.slot_len[0], tpl.prefix_len
+    ctx = Context(dims, tpl.slot_len, tpl.edges, P, B, F, 1)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    ctx.k_cache.normal_(generator=g)
+    ctx.v_cache.normal_(generator=g)
+    valid = np.full((B, F), S, dtype=np.int32)
+    ctx.set_valid_len(valid)
+    bf = np.tile(np.arange(F, dtype=np.int32), B)
+    bo = np.full(B * F, 32, dtype=np.int32)
+    M = B * F
+    q = torch.randn(M, dims.n_q_heads, dims.head_dim, generator=g, device="cuda").to(torch.bfloat16)
+    # algorithmic bytes: union of visible keys per (scene, kv head) x D x (K,V) x 2 B + Q read + O write
+    from paper_2602_02864_amd import fdc_build_mask
+    anc = fdc_build_mask(tpl.slot_len, tpl.edges, P)["anc_words"][:, 0]
+    union = P
+    for gfield in range(F):
+        seen_full = any((int(anc[f]) >> gfield) & 1 for f in range(F))
+        union += S if seen_full else 33          # own slot: offsets 0..32
+    kv_bytes = B * dims.n_kv_heads * union * dims.head_dim * 2 * 2
+    qo_bytes = M * dims.n_q_heads * dims.head_dim * (2 + 4)
+    alg_bytes = kv_bytes + qo_bytes
+    visible_pairs = sum(bin(int(a)).count("1") for a in anc) + F
+    K = 20 if quick else max(20, args.steps if args.steps > 0 else 100)
+    W = 3 if quick else max(3, args.warmup)
+    outs = [ctx.masked_attention(i % n_buf, q, bf, bo) for i in range(W)]
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(K):
+        out = ctx.masked_attention(i % n_buf, q, bf, bo)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / K
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    k_ms = prof["masked_attention"][0] / max(1, prof["masked_attention"][1])
+    ctx.close()
+    gbs = alg_bytes / (k_ms * 1e-3) / 1e9
+    return {"workload": f"cfg3: B=16, 32/8 heads x 128, prefix 4096, 16 branches x 64-token slots, "
+                        f"rho={rho}, dag_seed={args.dag_seed}",
+            "closure_density": round(visible_pairs / (F * F), 4),
+            "algorithmic_bytes": alg_bytes, "avg_us": round(k_ms * 1e3, 2),
+            "ms_per_call_stream": round(ms, 4), "launches": K,
+            "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def cpu_baseline(cfg_id):
+    """The oracle as it stands on this host's cores, bounded sample: the first
+    pass of the workload's schedule on a 2-layer cut of the model (+ final norm,
+    LM head, argmax); per-layer time scaled to the full depth."""
+    import oracle.fdc_oracle as O
+    from synth_inputs import (draw_layer_weights, draw_normal_bf16, model_dims, template,
+                              workload_seed)
+    full = model_dims(cfg_id)
+    nl = min(2, full.n_layers)
+    dims = model_dims(cfg_id, n_layers=nl)
+    tpl = template(cfg_id)
+    rng = workload_seed(cfg_id, "weights", 0)
+    w = {"layers": [draw_layer_weights(cfg_id, dims, l, random_gains=False) for l in range(nl)],
+         "emb": draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02),
+         "gf": np.ones(dims.d_model, dtype=np.float32),
+         "lm": draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)}
+    dec = O.OracleDecoder(dims, w, tpl.prefix_len, tpl.slot_len, tpl.edges)
+    prng = workload_seed(cfg_id, "prefix", 50)
+    shp = (nl, dims.n_kv_heads, tpl.prefix_len, dims.head_dim)
+    dec.set_prefix_kv(0, draw_normal_bf16(prng, shp), draw_normal_bf16(prng, shp))
+    st = O.schedule(tpl.n_fields, tpl.edges, tpl.content_len)[0]
+    bf = [f for f, _ in st]
+    bo = [o for _, o in st]
+    ti = [tpl.start_token[f] for f in bf]
+    # time layers and head separately so that the scaling to full depth is honest
+    t0 = time.perf_counter()
+    dec.step([bf], [bo], tok_in=np.array(ti).reshape(1, -1, 1))
+    t_all = time.perf_counter() - t0
+    one = model_dims(cfg_id, n_layers=1)
+    dec1 = O.OracleDecoder(one, {**w, "layers": w["layers"][:1]}, tpl.prefix_len, tpl.slot_len, tpl.edges)
+    dec1.set_prefix_kv(0, dec.K[:1, 0, :, :tpl.prefix_len], dec.V[:1, 0, :, :tpl.prefix_len])
+    t0 = time.perf_counter()
+    dec1.step([bf], [bo], tok_in=np.array(ti).reshape(1, -1, 1))
+    t_one = time.perf_counter() - t0
+    per_layer = max(t_all - t_one, 1e-9) / max(1, nl - 1) if nl > 1 else t_all
+    head = max(t_one - per_layer, 0.0)
+    t_full = per_layer * full.n_layers + head
+    cores = len(os.sched_getaffinity(0))
+    return {"value": round(len(bf) / t_full, 3), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first pass ({len(bf)} branches) of cfg{cfg_id} on a {nl}-layer cut, fp64 numpy; "
+                      f"measured {t_all:.2f}s for {nl} layers + head, {per_layer:.2f}s per layer, scaled to "
+                      f"{full.n_layers} layers = {t_full:.1f}s per pass"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the workload's whole schedule)")
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg0", "cfg1", "cfg2", "cfg3"])
+    ap.add_argument("--rho", type=float, default=0.3)
+    ap.add_argument("--dag-seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-attention", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path's sharding is described in DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    from paper_2602_02864_amd import lib
+    lib()                                            # fails loudly if the library is not built
+    if args.workload == "cfg3":
+        sweep = [run_attention(args, rho) for rho in (0.0, 0.1, 0.3, 1.0)]
+        main_r = [r for r in sweep if f"rho={args.rho}," in r["workload"]] or [sweep[2]]
+        a = main_r[0]
+        res = {"metric": "masked-attention HBM GB/s", "value": a["achieved"], "unit": "GB/s", "n_gpus": 1,
+               "steps": a["launches"], "warmup": max(3, args.warmup), "ms_per_step": a["avg_us"] / 1e3,
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+               "data": "synthetic", "config": {"workload": a["workload"]},
+               "roofline": {"bound": "hbm", "kernel": "masked_attention", "achieved": a["achieved"],
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a["frac"], "traffic": None},
+               "sweep": sweep}
+    else:
+        cfg_id = int(args.workload[3:])
+        res = run_decode(args, cfg_id)
+        if not args.no_attention:
+            res["attention"] = run_attention(args, quick=True)
+    if not args.no_cpu_baseline and args.workload != "cfg3":
+        t0 = time.time()
+        res["cpu_baseline"] = cpu_baseline(int(args.workload[3:]))
+        log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
+    elif args.workload == "cfg3" and not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_attention()
+    print(json.dumps(res), flush=True)
+
+
+def cpu_baseline_attention():
+    """Oracle attention of workload 3 on one scene, a few rows, scaled to all rows."""
+    import oracle.fdc_oracle as O
+    from synth_inputs import draw_normal_bf16, model_dims, template, workload_seed
+    dims = model_dims(3)
+    tpl = template(3, rho=0.3)
+    F, S, P = tpl.n_fields, tpl.slot_len[0], tpl.prefix_len
+    N = P + F * S
+    rng = workload_seed(3, "prefix", 7)
+    Kc = draw_normal_bf16(rng, (dims.n_kv_heads, N, dims.head_dim))
+    Vc = draw_normal_bf16(rng, (dims.n_kv_heads, N, dims.head_dim))
+    q = draw_normal_bf16(rng, (4, dims.n_q_heads, dims.head_dim))
+    t0 = time.perf_counter()
+    O.attention_only(q, Kc, Vc, P, tpl.slot_len, tpl.edges, [S] * F, [0, 5, 10, 15], [32] * 4, dims.group)
+    dt = time.perf_counter() - t0
+    t_full = dt / 4 * 16 * 16
+    alg = 16 * dims.n_kv_heads * N * dims.head_dim * 4
+    return {"value": round(alg / t_full / 1e9, 4), "unit": "GB/s", "cores": len(os.sched_getaffinity(0)),
+            "kind": "oracle", "sample": f"4 of 256 query rows of one scene, fp64 numpy: {dt:.2f}s, "
+                                        f"scaled to 256 rows = {t_full:.1f}s per call"}
+
+
+if __name__ == "__main__":
+    main()

@@ -24,8 +24,9 @@
  *    the tile order the kernels stream.
  *  - rows of a step are ordered m = (scene * R + branch) * T + t.
  *  - limits: n_fields <= 64 for a context; head_dim in {64, 128};
- *    d_model, n_q_heads*head_dim and d_mlp multiples of 32; B*R*T <= 16 rows per
- *    step for the dense projections (FDC_ECAP otherwise).
+ *    d_model, n_q_heads*head_dim and d_mlp multiples of 32, vocab of 4;
+ *    d_model <= 5120; B*R*T <= 16 rows per step for the dense projections
+ *    (FDC_ECAP otherwise).
  */
 #ifndef FDC_H
 #define FDC_H
@@ -111,13 +112,33 @@ int32_t fdc_dense_mask(int32_t n_fields, const int32_t* slot_len, const int32_t*
                        uint8_t* mask, int32_t* pos);
 
 /* ---------------------------------------------------------------------------
+ * Algorithm 1 (host only): in-degree counters and the ready set.  A field is
+ * "finished" after content_len[f] decoded tokens (the caller's stand-in for
+ * "the model ended the line"; at most the slot length).  Each fdc_sched_next
+ * returns the ready fields in field order with their next slot offset, pads the
+ * arrays [max_branches] with field -1, and then accounts one decoded token per
+ * ready field: finished fields leave the set and release successors whose last
+ * prerequisite they were.  *n_active == 0 means every field is complete.  The
+ * number of non-empty passes equals the critical-path length of the template.
+ * Errors: as fdc_build_mask for the graph; FDC_ECAP if more than max_branches
+ * fields are ready.
+ */
+typedef struct fdc_sched fdc_sched;
+int32_t fdc_sched_create(int32_t n_fields, int32_t n_edges, const int32_t* edge_src,
+                         const int32_t* edge_dst, const int32_t* content_len, fdc_sched** out);
+int32_t fdc_sched_next(fdc_sched* s, int32_t max_branches, int32_t* branch_field,
+                       int32_t* branch_off, int32_t* n_active);
+void    fdc_sched_destroy(fdc_sched* s);
+
+/* ---------------------------------------------------------------------------
  * Weight packing.  Streams a row-major bf16 matrix [n_out][k_in] (device) into
  * the 16x32-element tile order the projection kernels read with one contiguous
- * 1 KiB load per wavefront.  n_out multiple of 16, k_in multiple of 32.
+ * 1 KiB load per wavefront.  k_in multiple of 32; n_out is padded with zero
+ * rows to a multiple of 16 in dst.
  * FDC_PACK_GATE_UP interleaves the 16-row tiles of the gate half and the up
- * half of a [2*d_mlp][d_model] matrix so SwiGLU can be applied in the
- * projection's epilogue.  dst needs fdc_packed_weight_bytes(n_out, k_in) bytes
- * (= 2*n_out*k_in) and must not overlap src.
+ * half of a [2*d_mlp][d_model] matrix (n_out multiple of 32) so SwiGLU can be
+ * applied in the projection's epilogue.  dst needs
+ * fdc_packed_weight_bytes(n_out, k_in) bytes and must not overlap src.
  */
 #define FDC_PACK_PLAIN   0
 #define FDC_PACK_GATE_UP 1
@@ -225,6 +246,20 @@ int32_t fdc_argmax(const float* logits, int32_t M, int32_t V, int64_t ld,
 size_t  fdc_linear_scratch_bytes(int32_t M, int64_t n_out, int64_t k_in);
 int32_t fdc_linear(const float* x, const void* w_packed, float* y,
                    int32_t M, int64_t n_out, int64_t k_in, void* scratch, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Optional per-kernel timing for benchmarks (the paper times with device events,
+ * Sec. 4.1).  While enabled, every kernel launch of fdc_parallel_decode_step and
+ * fdc_masked_attention is bracketed by two HIP events on the caller's stream.
+ * fdc_profile_read waits for the recorded events, returns per kind the summed
+ * milliseconds and the number of launches since the last read, and clears them.
+ * masked_attention covers both of its kernels (partial + merge).
+ */
+#define FDC_PROF_KINDS 9
+int32_t     fdc_profile_enable(fdc_ctx* ctx, int32_t on);
+int32_t     fdc_profile_read(fdc_ctx* ctx, float* ms_sum /* host [FDC_PROF_KINDS] */,
+                             int32_t* launches /* host [FDC_PROF_KINDS] */);
+const char* fdc_profile_kind_name(int32_t kind);   /* NULL outside 0..FDC_PROF_KINDS-1 */
 
 #ifdef __cplusplus
 }

@@ -29,7 +29,10 @@ EXPORTS = [
     "fdc_set_layer_weights", "fdc_set_head_weights", "fdc_reset", "fdc_set_valid_len",
     "fdc_get_valid_len", "fdc_kv_append", "fdc_parallel_decode_step", "fdc_masked_attention",
     "fdc_argmax", "fdc_linear_scratch_bytes", "fdc_linear",
+    "fdc_profile_enable", "fdc_profile_read", "fdc_profile_kind_name",
+    "fdc_sched_create", "fdc_sched_next", "fdc_sched_destroy",
 ]
+FDC_PROF_KINDS = 9
 
 
 class FdcError(RuntimeError):
@@ -112,6 +115,18 @@ def lib() -> C.CDLL:
     L.fdc_linear_scratch_bytes.argtypes = [i32, i64, i64]
     L.fdc_linear.restype = i32
     L.fdc_linear.argtypes = [vp, vp, vp, i32, i64, i64, vp, vp]
+    L.fdc_profile_enable.restype = i32
+    L.fdc_profile_enable.argtypes = [vp, i32]
+    L.fdc_profile_read.restype = i32
+    L.fdc_profile_read.argtypes = [vp, C.POINTER(C.c_float), pi32]
+    L.fdc_profile_kind_name.restype = C.c_char_p
+    L.fdc_profile_kind_name.argtypes = [i32]
+    L.fdc_sched_create.restype = i32
+    L.fdc_sched_create.argtypes = [i32, i32, pi32, pi32, pi32, C.POINTER(vp)]
+    L.fdc_sched_next.restype = i32
+    L.fdc_sched_next.argtypes = [vp, i32, pi32, pi32, pi32]
+    L.fdc_sched_destroy.restype = None
+    L.fdc_sched_destroy.argtypes = [vp]
     _lib = L
     return L
 
@@ -164,6 +179,29 @@ def fdc_dense_mask(slot_len, slot_start, anc_words, prefix_len: int, valid_len, 
     _check(lib().fdc_dense_mask(sl.size, _p(sl), _p(ss), _p(anc, C.c_uint64), int(prefix_len), _p(vl),
                                 rf.size, _p(rf), _p(ro), _p(mask, C.c_uint8), _p(pos)))
     return mask, pos
+
+
+def fdc_schedule(n_fields: int, edges, content_len, max_branches: Optional[int] = None):
+    """Runs fdc_sched_* to completion; returns the list of passes, each a pair
+    (branch_field, branch_off) of int32 arrays of length max_branches."""
+    src, dst = _edges(edges)
+    cl = _i32(content_len)
+    R = max_branches or n_fields
+    h = C.c_void_p()
+    _check(lib().fdc_sched_create(n_fields, src.size, _p(src), _p(dst), _p(cl), C.byref(h)))
+    passes = []
+    try:
+        while True:
+            bf = np.zeros(R, dtype=np.int32)
+            bo = np.zeros(R, dtype=np.int32)
+            n = C.c_int32(0)
+            _check(lib().fdc_sched_next(h, R, _p(bf), _p(bo), C.byref(n)))
+            if n.value == 0:
+                break
+            passes.append((bf, bo))
+    finally:
+        lib().fdc_sched_destroy(h)
+    return passes
 
 
 # --------------------------------------------------------------------------- device
@@ -310,6 +348,16 @@ class Context:
         _check(lib().fdc_kv_append(self._h, layer, k.data_ptr(), v.data_ptr(), rs.data_ptr(),
                                    rp.data_ptr(), n, _stream()))
         torch.cuda.current_stream().synchronize()      # temporaries die here
+
+    def profile_enable(self, on: bool):
+        _check(lib().fdc_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self) -> dict:
+        ms = np.zeros(FDC_PROF_KINDS, dtype=np.float32)
+        n = np.zeros(FDC_PROF_KINDS, dtype=np.int32)
+        _check(lib().fdc_profile_read(self._h, _p(ms, C.c_float), _p(n)))
+        return {lib().fdc_profile_kind_name(k).decode(): (float(ms[k]), int(n[k]))
+                for k in range(FDC_PROF_KINDS)}
 
     # -- the step -------------------------------------------------------------------
     def parallel_decode_step(self, branch_field, branch_off, tok_in=None, emb_in=None, T: int = 1,

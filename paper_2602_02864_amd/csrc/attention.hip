@@ -55,14 +55,32 @@ __device__ __forceinline__ RowInfo row_info(int gr, int b, int kvh, int G, const
     return ri;
 }
 
-template <int D, int NRT>
+// two floats -> packed bf16 heads and packed bf16 tails (head + tail ~ value to 2^-17)
+__device__ __forceinline__ void split2(float x, float y, uint32_t& hi, uint32_t& lo) {
+    f32x2 v = {x, y};
+    hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    f32x2 r = {x - __uint_as_float(hi << 16), y - __uint_as_float(hi & 0xffff0000u)};
+    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
+}
+
+union Frag {
+    bf16x8 v;
+    uint32_t u[4];
+};
+
+// QF32: the queries come in fp32 (inside the decode step) and are used as bf16
+// head + tail; otherwise they are bf16 data and have no tail.  The softmax
+// weights are always used as head + tail, so the only bf16 rounding left in the
+// attention is the one the bf16 KV cache itself implies.
+template <int D, int NRT, bool QF32>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta sm) {
-    constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32;
+    constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, QP = QF32 ? 2 : 1;
     __shared__ uint16_t vis[NR][kMaxFields + 2];
     __shared__ uint16_t maxvis[kMaxFields];
     __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
     __shared__ float red_m[4][NR], red_l[4][NR];
     __shared__ f32x4 red_o[NRT * DT * 4 * 64];
+    __shared__ bf16x8 qs[NRT][DJ][QP][64];
 
     const int chunk = blockIdx.x, rg = blockIdx.y, z = blockIdx.z;
     const int b = z / a.Hkv, kvh = z % a.Hkv;
@@ -89,6 +107,31 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
         }
         vis[r][g] = (uint16_t)n;
     }
+    // query operand in LDS: fragment (rt, j) holds, per lane, row rt*32 + lane%32,
+    // d = 16*j + 8*(lane/32) + 0..7
+    for (int idx = wave; idx < NRT * DJ; idx += 4) {
+        const int rt = idx / DJ, j = idx % DJ;
+        const int r = rt * 32 + r32;
+        const int m = row_m[r];
+        Frag fh, fl;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) fh.u[k] = fl.u[k] = 0;
+        if (m >= 0) {
+            const size_t qo = ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh;
+            if (QF32) {
+                const f32x4 q0 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo);
+                const f32x4 q1 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 4);
+                split2(q0[0], q0[1], fh.u[0], fl.u[0]);
+                split2(q0[2], q0[3], fh.u[1], fl.u[1]);
+                split2(q1[0], q1[1], fh.u[2], fl.u[2]);
+                split2(q1[2], q1[3], fh.u[3], fl.u[3]);
+            } else {
+                fh.v = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo);
+            }
+        }
+        qs[rt][j][0][lane] = fh.v;
+        if (QF32) qs[rt][j][QP - 1][lane] = fl.v;
+    }
     __syncthreads();
     if (tid < F) {
         int mx = 0;
@@ -96,22 +139,6 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
         maxvis[tid] = (uint16_t)mx;
     }
     __syncthreads();
-
-    // query operand: lane holds row (rt*32 + r32), d = 16*j + 8*hh + 0..7
-    bf16x8 qf[NRT][DJ];
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-        const int r = rt * 32 + r32;
-        const int m = row_m[r];
-#pragma unroll
-        for (int j = 0; j < DJ; ++j) {
-            bf16x8 zq = {0, 0, 0, 0, 0, 0, 0, 0};
-            qf[rt][j] = zq;
-            if (m >= 0)
-                qf[rt][j] = *reinterpret_cast<const bf16x8*>(
-                    a.q + ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh);
-        }
-    }
 
     f32x16 o[NRT][DT];
     float m_run[NRT], l_run[NRT];
@@ -127,7 +154,59 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
 
     const int blk_end = min(a.NB, (chunk + 1) * a.CB);
     const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
-    for (int blk = chunk * a.CB + wave; blk < blk_end; blk += 4) {
+
+    // a tile that reaches into the slots is fetched only if some row of the row
+    // tile can see one of its keys (wave-uniform answer)
+    auto tile_active = [&](int blk) -> bool {
+        const int key0 = blk * 32;
+        if (key0 + 32 <= a.P) return true;
+        bool mine = false;
+        if (lane < 32) {
+            const int key = key0 + lane;
+            if (key < a.P) mine = true;
+            else {
+                const uint32_t tab = a.slot_tab[key - a.P];
+                mine = tab != 0xffffffffu && (tab >> 8) < maxvis[tab & 0xff];
+            }
+        }
+        return __any(mine);
+    };
+    auto load_tile = [&](int blk, bf16x8 (&kf)[DJ], bf16x8 (&vf)[DT][2]) {
+        const uint16_t* kt = a.kc + (tile_base + blk) * (32 * D);
+        const uint16_t* vt = a.vc + (tile_base + blk) * (32 * D);
+#pragma unroll
+        for (int j = 0; j < DJ; ++j)
+            kf[j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(kt + (j * 64 + lane) * 8));
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                vf[dt][s] = __builtin_nontemporal_load(
+                    reinterpret_cast<const bf16x8*>(vt + ((dt * 2 + s) * 64 + lane) * 8));
+    };
+
+    int blk = chunk * a.CB + wave;
+    while (blk < blk_end && !tile_active(blk)) blk += 4;
+    bf16x8 kn[DJ], vn[DT][2];
+    if (blk < blk_end) load_tile(blk, kn, vn);
+
+    while (blk < blk_end) {
+        // keeps the query fragments in LDS (re-read per tile) instead of letting
+        // the compiler hoist them into 64-128 registers for the whole loop
+        asm volatile("" ::: "memory");
+        bf16x8 kf[DJ], vf[DT][2];
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) kf[j] = kn[j];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            vf[dt][0] = vn[dt][0];
+            vf[dt][1] = vn[dt][1];
+        }
+        // next tile of this wavefront: issue its loads before computing on this one
+        int nxt = blk + 4;
+        while (nxt < blk_end && !tile_active(nxt)) nxt += 4;
+        if (nxt < blk_end) load_tile(nxt, kn, vn);
+
         const int key0 = blk * 32;
         const bool masked = key0 + 32 > a.P;          // tile reaches into the slots
         // register i of this lane belongs to key0 + 8*(i/4) + 4*hh + i%4.  For a
@@ -151,40 +230,23 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
                 }
                 anybits |= (v ? 1u : 0u) << i;
             }
-            if (!__any(anybits != 0)) continue;       // nobody sees this tile: never fetched
-        }
-        const uint16_t* kt = a.kc + (tile_base + blk) * (32 * D);
-        const uint16_t* vt = a.vc + (tile_base + blk) * (32 * D);
-        bf16x8 kf[DJ], vf[DT][2];
+            if (anybits != 0xffffu) {
+                // zero the V columns of keys nobody sees (0 * garbage must stay 0)
 #pragma unroll
-        for (int j = 0; j < DJ; ++j)
-            kf[j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(kt + (j * 64 + lane) * 8));
+                for (int s = 0; s < 2; ++s) {
+                    uint32_t wm[4];
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+                    for (int k = 0; k < 4; ++k)
+                        wm[k] = ((anybits >> (8 * s + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
+                                ((anybits >> (8 * s + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
-                vf[dt][s] = __builtin_nontemporal_load(
-                    reinterpret_cast<const bf16x8*>(vt + ((dt * 2 + s) * 64 + lane) * 8));
-
-        if (masked && anybits != 0xffffu) {
-            // zero the V columns of keys nobody sees (0 * garbage must stay 0)
+                    for (int dt = 0; dt < DT; ++dt) {
+                        Frag cv;
+                        cv.v = vf[dt][s];
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                uint32_t wm[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    wm[k] = ((anybits >> (8 * s + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
-                            ((anybits >> (8 * s + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    union {
-                        bf16x8 v;
-                        uint32_t u[4];
-                    } cv;
-                    cv.v = vf[dt][s];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) cv.u[k] &= wm[k];
-                    vf[dt][s] = cv.v;
+                        for (int k = 0; k < 4; ++k) cv.u[k] &= wm[k];
+                        vf[dt][s] = cv.v;
+                    }
                 }
             }
         }
@@ -194,8 +256,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
 #pragma unroll
             for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
-            for (int j = 0; j < DJ; ++j)
-                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[rt][j], sc, 0, 0, 0);
+            for (int j = 0; j < DJ; ++j) {
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qs[rt][j][0][lane], sc, 0, 0, 0);
+                if (QF32)
+                    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qs[rt][j][QP - 1][lane], sc, 0, 0, 0);
+            }
             uint32_t vbits = 0xffffu;
             if (masked) {
                 vbits = 0;
@@ -220,34 +285,34 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
             const float alpha = exp2f(m_run[rt] - m_new);
             m_run[rt] = m_new;
             float psum = 0.f;
-            uint16_t pb[16];
+            float p[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float p = (vbits >> i & 1u) ? exp2f(sc[i] - m_new) : 0.f;
-                psum += p;
-                pb[i] = f2bf(p);
+                p[i] = (vbits >> i & 1u) ? exp2f(sc[i] - m_new) : 0.f;
+                psum += p[i];
             }
             l_run[rt] = l_run[rt] * alpha + psum;
-            bf16x8 pf[2];
+            Frag ph[2], pl[2];
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                union {
-                    uint16_t u[8];
-                    bf16x8 v;
-                } cv;
+            for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) cv.u[e] = pb[8 * s + e];
-                pf[s] = cv.v;
-            }
+                for (int k = 0; k < 4; ++k)
+                    split2(p[8 * s + 2 * k], p[8 * s + 2 * k + 1], ph[s].u[k], pl[s].u[k]);
+            const bool rescale = __any(alpha != 1.0f);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
+                if (rescale) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[rt][dt][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) o[rt][dt][i] *= alpha;
+                }
 #pragma unroll
-                for (int s = 0; s < 2; ++s)
-                    o[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], pf[s], o[rt][dt], 0, 0, 0);
+                for (int s = 0; s < 2; ++s) {
+                    o[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], ph[s].v, o[rt][dt], 0, 0, 0);
+                    o[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], pl[s].v, o[rt][dt], 0, 0, 0);
+                }
             }
         }
+        blk = nxt;
     }
 
     // ---- merge the four wavefronts (fixed order), emit one partial ---------------
@@ -257,12 +322,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
         if (hh == 0) red_m[wave][rt * 32 + r32] = m_run[rt];
     }
     __syncthreads();
-    float mg[NRT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
         const int r = rt * 32 + r32;
-        mg[rt] = fmaxf(fmaxf(red_m[0][r], red_m[1][r]), fmaxf(red_m[2][r], red_m[3][r]));
-        const float sc = exp2f(m_run[rt] - mg[rt]);
+        const float mg = fmaxf(fmaxf(red_m[0][r], red_m[1][r]), fmaxf(red_m[2][r], red_m[3][r]));
+        const float sc = exp2f(m_run[rt] - mg);
         if (hh == 0) red_l[wave][r] = l_run[rt] * sc;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -353,8 +417,12 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm
 template <int D, int NRT>
 void launch_t(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
     const int z = sm.B * a.Hkv;
-    hipLaunchKernelGGL((attn_partial_kernel<D, NRT>), dim3(a.n_chunks, a.n_rg, z), dim3(256), 0, st,
-                       a, sm);
+    if (a.q_f32)
+        hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), dim3(a.n_chunks, a.n_rg, z), dim3(256),
+                           0, st, a, sm);
+    else
+        hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), dim3(a.n_chunks, a.n_rg, z), dim3(256),
+                           0, st, a, sm);
     constexpr int Q4 = NRT * (D / 32) * 4 * 64;
     hipLaunchKernelGGL((attn_merge_kernel<D, NRT>), dim3((Q4 + 255) / 256, z * a.n_rg), dim3(256), 0,
                        st, a, sm);

@@ -58,9 +58,43 @@ struct fdc_ctx {
     bool stage_used[kStageSlots] = {};
     int stage_next = 0;
 
+    // optional per-kernel timing with HIP events (benchmarks only)
+    bool prof_on = false;
+    struct ProfRec { int kind; hipEvent_t e0, e1; };
+    std::vector<ProfRec> prof_recs;      // recorded since the last read
+    std::vector<ProfRec> prof_pool;      // idle event pairs
+
     template <class T>
     T* at(size_t o) const { return reinterpret_cast<T*>(ws + o); }
 };
+
+namespace {
+// brackets one kernel launch with two events when profiling is on
+struct ProfScope {
+    fdc_ctx* c;
+    hipStream_t st;
+    fdc_ctx::ProfRec r{};
+    bool live = false;
+    ProfScope(fdc_ctx* c_, int kind, hipStream_t st_) : c(c_), st(st_) {
+        if (!c->prof_on) return;
+        if (!c->prof_pool.empty()) {
+            r = c->prof_pool.back();
+            c->prof_pool.pop_back();
+        } else if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) {
+            return;
+        }
+        r.kind = kind;
+        live = hipEventRecord(r.e0, st) == hipSuccess;
+    }
+    ~ProfScope() {
+        if (!live) return;
+        (void)hipEventRecord(r.e1, st);
+        c->prof_recs.push_back(r);
+    }
+};
+enum { PK_NORM = 0, PK_QKV, PK_ROPE, PK_ATTN, PK_O, PK_GATEUP, PK_DOWN, PK_LMHEAD, PK_ARGMAX, PK_COUNT };
+static_assert(PK_COUNT == FDC_PROF_KINDS, "profile kinds");
+}  // namespace
 
 namespace {
 
@@ -105,7 +139,7 @@ size_t carve(fdc_ctx* c) {
     c->off.o_lo = take(2 * (size_t)Mp * HqD);
     c->off.h_hi = take(2 * (size_t)Mp * m.d_mlp);
     c->off.h_lo = take(2 * (size_t)Mp * m.d_mlp);
-    c->off.q = take(2 * (size_t)c->Mmax * HqD);
+    c->off.q = take(sizeof(float) * (size_t)kMaxRowsDense * HqD);
     size_t part = 0;
     part = std::max(part, (size_t)c->p_qkv.S * Mp * Nqkv);
     part = std::max(part, (size_t)c->p_o.S * Mp * m.d_model);
@@ -330,6 +364,11 @@ int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t*
 
 void fdc_destroy(fdc_ctx* c) {
     if (!c) return;
+    for (auto* v : {&c->prof_recs, &c->prof_pool})
+        for (auto& r : *v) {
+            (void)hipEventDestroy(r.e0);
+            (void)hipEventDestroy(r.e1);
+        }
     for (int i = 0; i < kStageSlots; ++i) {
         if (c->stage_ev[i]) {
             (void)hipEventSynchronize(c->stage_ev[i]);
@@ -452,9 +491,12 @@ int32_t fdc_masked_attention(fdc_ctx* c, int32_t layer, const void* q, int32_t R
     if (rc != FDC_OK) return rc;
     AttnArgs a;
     fill_attn(c, layer, R, T, &a);
-    a.q = (const uint16_t*)q;
+    a.q_bf16 = (const uint16_t*)q;
     a.out_f32 = out;
-    launch_attention(a, sm, st);
+    {
+        ProfScope ps_(c, PK_ATTN, st);
+        launch_attention(a, sm, st);
+    }
     FDC_HIP(hipGetLastError());
     return FDC_OK;
 }
@@ -499,7 +541,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     uint16_t *a_hi = c->at<uint16_t>(c->off.a_hi), *a_lo = c->at<uint16_t>(c->off.a_lo);
     uint16_t *o_hi = c->at<uint16_t>(c->off.o_hi), *o_lo = c->at<uint16_t>(c->off.o_lo);
     uint16_t *h_hi = c->at<uint16_t>(c->off.h_hi), *h_lo = c->at<uint16_t>(c->off.h_lo);
-    uint16_t* q = c->at<uint16_t>(c->off.q);
+    float* q = c->at<float>(c->off.q);
     float* logits = logits_out ? logits_out : c->at<float>(c->off.logits);
     const size_t hstride = (size_t)M * d;
 
@@ -526,7 +568,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         }
         n1.gain = w.g1;
         n1.hidden_x = hidden_out ? hidden_out + (size_t)l * hstride : nullptr;
-        launch_resid_norm(n1, sm, st);
+        { ProfScope ps_(c, PK_NORM, st); launch_resid_norm(n1, sm, st); }
 
         GemmArgs g{};
         g.w = (const uint16_t*)w.wqkv;
@@ -536,7 +578,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         g.M = M;
         g.N = Nqkv;
         g.n_valid = Nqkv;
-        launch_gemm(c->p_qkv, EPI_PARTIAL, g, st);
+        { ProfScope ps_(c, PK_QKV, st); launch_gemm(c->p_qkv, EPI_PARTIAL, g, st); }
 
         RopeArgs ra{};
         ra.part = part;
@@ -550,27 +592,27 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         ra.Hkv = m.n_kv_heads;
         ra.D = m.head_dim;
         ra.NB = c->NB;
-        launch_rope_append(ra, sm, st);
+        { ProfScope ps_(c, PK_ROPE, st); launch_rope_append(ra, sm, st); }
 
         AttnArgs aa;
         fill_attn(c, l, R, T, &aa);
-        aa.q = q;
+        aa.q_f32 = q;
         aa.out_hi = o_hi;
         aa.out_lo = o_lo;
-        launch_attention(aa, sm, st);
+        { ProfScope ps_(c, PK_ATTN, st); launch_attention(aa, sm, st); }
 
         g.w = (const uint16_t*)w.wo;
         g.act_hi = o_hi;
         g.act_lo = o_lo;
         g.N = d;
         g.n_valid = d;
-        launch_gemm(c->p_o, EPI_PARTIAL, g, st);
+        { ProfScope ps_(c, PK_O, st); launch_gemm(c->p_o, EPI_PARTIAL, g, st); }
 
         NormArgs n2 = na;
         n2.part = part;
         n2.S = c->p_o.S;
         n2.gain = w.g2;
-        launch_resid_norm(n2, sm, st);
+        { ProfScope ps_(c, PK_NORM, st); launch_resid_norm(n2, sm, st); }
 
         GemmArgs gu{};
         gu.w = (const uint16_t*)w.wgu;
@@ -580,14 +622,14 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         gu.out_lo = h_lo;
         gu.out_KT = m.d_mlp / 32;
         gu.M = M;
-        launch_gemm(c->p_gu, EPI_SWIGLU, gu, st);
+        { ProfScope ps_(c, PK_GATEUP, st); launch_gemm(c->p_gu, EPI_SWIGLU, gu, st); }
 
         g.w = (const uint16_t*)w.wd;
         g.act_hi = h_hi;
         g.act_lo = h_lo;
         g.N = d;
         g.n_valid = d;
-        launch_gemm(c->p_down, EPI_PARTIAL, g, st);
+        { ProfScope ps_(c, PK_DOWN, st); launch_gemm(c->p_down, EPI_PARTIAL, g, st); }
     }
     NormArgs nf = na;
     nf.part = part;
@@ -595,7 +637,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     nf.gain = c->gf;
     nf.hidden_x = hidden_out ? hidden_out + (size_t)m.n_layers * hstride : nullptr;
     nf.hidden_n = hidden_out ? hidden_out + (size_t)(m.n_layers + 1) * hstride : nullptr;
-    launch_resid_norm(nf, sm, st);
+    { ProfScope ps_(c, PK_NORM, st); launch_resid_norm(nf, sm, st); }
 
     GemmArgs gl{};
     gl.w = c->lm;
@@ -605,13 +647,45 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     gl.M = M;
     gl.N = m.vocab;
     gl.n_valid = m.vocab;
-    launch_gemm(c->p_lm, EPI_PARTIAL, gl, st);
-    launch_argmax(logits, M, m.vocab, m.vocab, tok_out, gap_out, sm.branch_field, T, st);
+    { ProfScope ps_(c, PK_LMHEAD, st); launch_gemm(c->p_lm, EPI_PARTIAL, gl, st); }
+    { ProfScope ps_(c, PK_ARGMAX, st); launch_argmax(logits, M, m.vocab, m.vocab, tok_out, gap_out, sm.branch_field, T, st); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         c->valid_len = saved;
         return fail(FDC_EHIP, "kernel launch failed: %s", hipGetErrorString(e));
     }
+    return FDC_OK;
+}
+
+int32_t fdc_profile_enable(fdc_ctx* c, int32_t on) {
+    if (!c) return fail(FDC_EINVAL, "null context");
+    c->prof_on = on != 0;
+    return FDC_OK;
+}
+
+const char* fdc_profile_kind_name(int32_t kind) {
+    static const char* names[PK_COUNT] = {"resid_norm", "qkv_proj", "rope_append", "masked_attention",
+                                          "o_proj", "gate_up_swiglu", "down_proj", "lm_head", "argmax"};
+    return kind >= 0 && kind < PK_COUNT ? names[kind] : nullptr;
+}
+
+int32_t fdc_profile_read(fdc_ctx* c, float* ms_sum, int32_t* launches) {
+    if (!c || !ms_sum || !launches) return fail(FDC_EINVAL, "null pointer argument");
+    for (int k = 0; k < FDC_PROF_KINDS; ++k) {
+        ms_sum[k] = 0.f;
+        launches[k] = 0;
+    }
+    for (auto& r : c->prof_recs) {
+        FDC_HIP(hipEventSynchronize(r.e1));
+        float ms = 0.f;
+        FDC_HIP(hipEventElapsedTime(&ms, r.e0, r.e1));
+        if (r.kind >= 0 && r.kind < FDC_PROF_KINDS) {
+            ms_sum[r.kind] += ms;
+            launches[r.kind] += 1;
+        }
+        c->prof_pool.push_back(r);
+    }
+    c->prof_recs.clear();
     return FDC_OK;
 }
 

@@ -81,7 +81,86 @@ int32_t build_plan(int32_t F, const int32_t* slot_len, int32_t E, const int32_t*
 
 }  // namespace fdc
 
+// Algorithm 1 as a host object: in-degree counters, the ready set, and one
+// token per ready field per pass.
+struct fdc_sched {
+    int F = 0;
+    std::vector<int32_t> indeg, done, content_len;
+    std::vector<std::vector<int32_t>> succ;
+    std::vector<char> ready, finished;
+    int64_t passes = 0, tokens = 0;
+};
+
 extern "C" {
+
+int32_t fdc_sched_create(int32_t F, int32_t E, const int32_t* src, const int32_t* dst,
+                         const int32_t* content_len, fdc_sched** out) {
+    if (!out) return fdc::fail(FDC_EINVAL, "null pointer argument");
+    *out = nullptr;
+    if (F < 1 || !content_len) return fdc::fail(FDC_EINVAL, "bad field list");
+    std::vector<int32_t> ones(F, 1), start(F);
+    std::vector<uint64_t> anc((size_t)F * ((F + 63) / 64));
+    int32_t total = 0;
+    int32_t rc = fdc::build_plan(F, ones.data(), E, src, dst, 0, anc.data(), start.data(), nullptr, &total);
+    if (rc != FDC_OK) return rc;
+    for (int f = 0; f < F; ++f)
+        if (content_len[f] < 1) return fdc::fail(FDC_EINVAL, "content_len[%d] = %d must be >= 1", f, content_len[f]);
+    fdc_sched* s = new fdc_sched;
+    s->F = F;
+    s->indeg.assign(F, 0);
+    s->done.assign(F, 0);
+    s->content_len.assign(content_len, content_len + F);
+    s->succ.resize(F);
+    s->ready.assign(F, 0);
+    s->finished.assign(F, 0);
+    // duplicate edges count once
+    std::vector<char> seen((size_t)F * F, 0);
+    for (int e = 0; e < E; ++e) {
+        if (seen[(size_t)src[e] * F + dst[e]]) continue;
+        seen[(size_t)src[e] * F + dst[e]] = 1;
+        s->indeg[dst[e]]++;
+        s->succ[src[e]].push_back(dst[e]);
+    }
+    for (int f = 0; f < F; ++f) s->ready[f] = s->indeg[f] == 0;
+    *out = s;
+    return FDC_OK;
+}
+
+void fdc_sched_destroy(fdc_sched* s) { delete s; }
+
+int32_t fdc_sched_next(fdc_sched* s, int32_t max_branches, int32_t* branch_field,
+                       int32_t* branch_off, int32_t* n_active) {
+    if (!s || !branch_field || !branch_off || !n_active) return fdc::fail(FDC_EINVAL, "null pointer argument");
+    int n = 0;
+    for (int f = 0; f < s->F; ++f) n += s->ready[f] ? 1 : 0;
+    if (n > max_branches) return fdc::fail(FDC_ECAP, "%d fields are ready, room for %d", n, max_branches);
+    int i = 0;
+    for (int f = 0; f < s->F; ++f)
+        if (s->ready[f]) {
+            branch_field[i] = f;
+            branch_off[i] = s->done[f];
+            ++i;
+        }
+    for (int j = i; j < max_branches; ++j) {
+        branch_field[j] = -1;
+        branch_off[j] = 0;
+    }
+    *n_active = n;
+    if (n == 0) return FDC_OK;
+    s->passes++;
+    s->tokens += n;
+    // every ready field has decoded one token; finished ones release their successors
+    std::vector<int32_t> fin;
+    for (int f = 0; f < s->F; ++f)
+        if (s->ready[f] && ++s->done[f] >= s->content_len[f]) fin.push_back(f);
+    for (int f : fin) {
+        s->ready[f] = 0;
+        s->finished[f] = 1;
+        for (int u : s->succ[f])
+            if (--s->indeg[u] == 0) s->ready[u] = 1;
+    }
+    return FDC_OK;
+}
 
 const char* fdc_strerror(int32_t code) {
     switch (code) {

@@ -59,7 +59,7 @@ void launch_resid_norm(const NormArgs& a, const StepMeta& sm, hipStream_t st);
 struct RopeArgs {
     const float* part;        // QKV partials [S][M][Nqkv]
     int S;
-    uint16_t* q;              // bf16 [M][Hq][D] rotated queries
+    float* q;                 // fp32 [M][Hq][D] rotated queries
     uint16_t* kc;             // layer base of the K cache
     uint16_t* vc;
     const double* inv_freq;   // [D/2]
@@ -76,7 +76,8 @@ void launch_argmax(const float* logits, int M, int V, int64_t ld, int32_t* idx, 
 
 // ---- attention (attention.hip) -------------------------------------------------
 struct AttnArgs {
-    const uint16_t* q;        // bf16 [M][Hq][D]
+    const uint16_t* q_bf16;   // queries [M][Hq][D]: bf16 data ...
+    const float* q_f32;       // ... or fp32 (used as bf16 head + tail)
     const uint16_t* kc;       // layer base
     const uint16_t* vc;
     float* part_o;            // [z*n_rg][n_chunks][NR*D]

@@ -71,7 +71,7 @@ __device__ __forceinline__ void cache_store(uint16_t* kc, uint16_t* vc, int scen
 
 // One workgroup per row: sum the QKV partials, rotate q and k by the row's
 // position id (slot_start[field] + offset: fixed by the template, Sec. 3.3),
-// store q (bf16) and append k, v to the cache at index = position id.
+// store q (fp32) and append k, v (bf16) to the cache at index = position id.
 template <int D>
 __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta sm) {
     const int m = blockIdx.x;
@@ -96,9 +96,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta s
         const float c = (float)cs, sf = (float)sn;
         const float y1 = x1 * c - x2 * sf, y2 = x2 * c + x1 * sf;
         if (hd < a.Hq) {
-            uint16_t* q = a.q + ((size_t)m * a.Hq + hd) * D;
-            q[i] = f2bf(y1);
-            q[i + half] = f2bf(y2);
+            float* q = a.q + ((size_t)m * a.Hq + hd) * D;
+            q[i] = y1;
+            q[i + half] = y2;
         } else {
             const int kvh = hd - a.Hq;
             cache_store<D>(a.kc, a.vc, scene, kvh, a.Hkv, a.NB, pos, i, true, f2bf(y1));

@@ -89,6 +89,33 @@ def test_workload_templates_masks_match_oracle():
         assert np.array_equal(mask.astype(bool), want_mask) and np.array_equal(pos, want_pos)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_scheduler_matches_oracle_algorithm1(seed):
+    """Same passes, same (field, offset) sets as the oracle's Algorithm 1, and
+    as many passes as the critical path is long (Sec. 3.2)."""
+    from paper_2602_02864_amd import fdc_schedule
+    tpl = random_dag_template(700 + seed, n_fields=2 + 2 * seed, prefix_len=0, max_slot=7,
+                              edge_prob=0.3, vocab=10)
+    F = tpl.n_fields
+    want = O.schedule(F, tpl.edges, tpl.content_len)
+    got = fdc_schedule(F, tpl.edges + tpl.edges[:2], tpl.content_len)
+    assert len(got) == len(want)
+    for (bf, bo), st in zip(got, want):
+        n = len(st)
+        assert [(int(f), int(o)) for f, o in zip(bf[:n], bo[:n])] == st
+        assert (bf[n:] == -1).all()
+    cp = [0] * F
+    for f in range(F):
+        cp[f] = tpl.content_len[f] + max([cp[u] for (u, v) in tpl.edges if v == f], default=0)
+    assert len(got) == max(cp)
+    with pytest.raises(FdcError) as e:
+        fdc_schedule(3, [], [1, 1, 1], max_branches=2)
+    assert e.value.code == fb.FDC_ECAP
+    with pytest.raises(FdcError) as e:
+        fdc_schedule(2, [(0, 1), (1, 0)], [1, 1])
+    assert e.value.code == fb.FDC_ECYCLE
+
+
 def test_build_mask_error_codes():
     def code(*a):
         with pytest.raises(FdcError) as e:
