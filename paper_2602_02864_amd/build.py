@@ -21,6 +21,9 @@ SOURCES = ["fdc_host.cpp", "fdc_api.hip", "gemm_skinny.hip", "rowops.hip", "atte
 
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             # matrix-instruction accumulators in ordinary VGPRs: the softmax rescales
+             # them with vector ALU ops, which cannot touch accumulation registers
+             "-mllvm", "-amdgpu-mfma-vgpr-form=1",
              "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -1,29 +1,35 @@
 // DAG-masked GQA decode attention over the field-slot KV cache (Sec. 3.3).
 //
 // All query rows that share a KV head - every active branch of a scene, its T
-// new tokens and the G query heads of the group - form one row tile, so the
-// shared prefix and every visible slot are streamed from HBM once for all of
-// them (the paper's "shared KV cache accessed by multiple query tokens within a
-// single attention kernel").  The key dimension is cut into chunks (split-K);
-// a workgroup of four wavefronts takes one chunk of one (scene, kv head, row
-// group), its wavefronts take the chunk's 32-key tiles round-robin, merge
-// their softmax states through LDS in a fixed order and emit one partial.  A
-// second kernel merges the chunks' partials in chunk order (no atomics: results
-// are bit-reproducible).
+// new tokens and the G query heads of the group - form one row group of up to
+// 64 rows, so the shared prefix and every visible slot are streamed from HBM
+// once for all of them (the paper's "shared KV cache accessed by multiple query
+// tokens within a single attention kernel").  The key dimension is cut into
+// chunks (split-K); one workgroup takes one chunk of one (scene, kv head, row
+// group) and emits one partial softmax state; a second kernel merges the
+// chunks' partials in a fixed order (no atomics: results are bit-reproducible).
 //
-// The mask is never materialised.  A row of field f at slot offset t sees
-//   the prefix, the first valid_len[g] keys of each strict ancestor slot g, and
-//   the first t+1 keys of its own slot;
-// i.e. a *count* of visible keys per slot.  The kernel builds that count table
-// in LDS from the ancestor bit words, skips every 32-key tile no row of the
-// tile can see, runs prefix tiles without any masking, and masks slot tiles
-// per key with one table lookup.
+// Inside a workgroup two independent tile streams run side by side (even / odd
+// active tiles of the chunk).  A stream is NRT wavefronts, one per 32-row tile;
+// they share each 32-key K/V tile through LDS.  Tiles are copied HBM -> LDS
+// with the direct-to-LDS load (no registers involved) into a three-stage ring,
+// so two tiles per stream are always in flight while a third is consumed.  The
+// cache stores tiles in matrix-operand order, so one load instruction moves a
+// contiguous 1 KiB and the LDS image is read back conflict-free.
+//
+// The mask is never materialised in memory.  A row of field f at slot offset t
+// sees the prefix, the first valid_len[g] keys of each strict ancestor slot g
+// and the first t+1 keys of its own slot - a *count* of visible keys per slot.
+// At start-up the workgroup turns those counts into one 32-bit visibility word
+// per (row, tile) for the few tiles that reach into the slots; tiles no row can
+// see are never fetched, prefix tiles run without any masking.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16): S^T = K * Q^T puts one query
 // row in each lane (column = lane % 32), so the running max / sum are in-lane
 // plus one exchange with lane ^ 32; the score registers are, unchanged, the
 // P^T operand of O^T = V^T * P^T because the V tiles are stored in that key
-// order.  K and V tiles are contiguous 1 KiB pieces per load instruction.
+// order.  Softmax weights (and fp32 queries) enter the matrix cores as a bf16
+// head plus a bf16 tail, so the only bf16 rounding left is that of the cache.
 #include "kernels_common.hpp"
 #include "fdc_launch.hpp"
 
@@ -32,6 +38,8 @@ namespace fdc {
 namespace {
 
 constexpr float kNegBig = -1.0e30f;
+constexpr int kStages = 3;
+constexpr int kStreams = 2;
 
 struct RowInfo {
     int m;       // global row of the step, or -1 if the row does not exist / is inactive
@@ -55,6 +63,11 @@ __device__ __forceinline__ RowInfo row_info(int gr, int b, int kvh, int G, const
     return ri;
 }
 
+union Frag {
+    bf16x8 v;
+    uint32_t u[4];
+};
+
 // two floats -> packed bf16 heads and packed bf16 tails (head + tail ~ value to 2^-17)
 __device__ __forceinline__ void split2(float x, float y, uint32_t& hi, uint32_t& lo) {
     f32x2 v = {x, y};
@@ -63,41 +76,79 @@ __device__ __forceinline__ void split2(float x, float y, uint32_t& hi, uint32_t&
     lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2));
 }
 
-union Frag {
-    bf16x8 v;
-    uint32_t u[4];
-};
+// bits of a 32-key visibility word that belong to this lane's 16 score registers:
+// register i <-> key 8*(i/4) + 4*hh + i%4
+__device__ __forceinline__ uint32_t lane_bits(uint32_t word, int hh) {
+    const uint32_t x = word >> (4 * hh);
+    return (x & 0xfu) | ((x >> 4) & 0xf0u) | ((x >> 8) & 0xf00u) | ((x >> 12) & 0xf000u);
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void glb_void;
+
+// LDS accesses of the main loop are written out by hand.  The tile copies are
+// asynchronous (direct-to-LDS loads counted by vmcnt) and stay in flight across
+// iterations; letting the compiler see LDS reads there would make it wait for
+// *all* outstanding copies before each of them.  So the loop uses raw LDS
+// offsets, its own s_waitcnt and a bare s_barrier.
+__device__ __forceinline__ uint32_t lds_off(const void* p) {
+    return (uint32_t)(uintptr_t)(lds_void*)p;
+}
+__device__ __forceinline__ void lds_read128(Frag& f, uint32_t off) {
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(off));
+}
+__device__ __forceinline__ uint32_t lds_read32(uint32_t off) {
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(off));
+    return v;
+}
+// value of the lane 32 away (v_permlane32_swap exchanges the upper half of its
+// first operand with the lower half of its second)
+__device__ __forceinline__ float other_half(float x, int hh) {
+    const uint32_t u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(hh ? r[0] : r[1]);
+}
 
 // QF32: the queries come in fp32 (inside the decode step) and are used as bf16
-// head + tail; otherwise they are bf16 data and have no tail.  The softmax
-// weights are always used as head + tail, so the only bf16 rounding left in the
-// attention is the one the bf16 KV cache itself implies.
+// head + tail; otherwise they are bf16 data and have no tail.
 template <int D, int NRT, bool QF32>
-__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta sm) {
-    constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, QP = QF32 ? 2 : 1;
+__global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnArgs a, StepMeta sm) {
+    constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, NT = kStreams * NRT * 64;
+    constexpr int TILE = 32 * D;                    // bf16 elements of one K (or V) tile
+    constexpr int LPT = 2 * DJ;                     // 1 KiB load instructions per K+V tile
+    constexpr int LPW = LPT / NRT;                  // ... issued by each wavefront of a stream
+    __shared__ __attribute__((aligned(16))) uint16_t stage[kStreams][kStages][2 * TILE];
     __shared__ uint16_t vis[NR][kMaxFields + 2];
-    __shared__ uint16_t maxvis[kMaxFields];
+    __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
+    __shared__ uint32_t tile_any[kMaxMaskedTiles];
     __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
-    __shared__ float red_m[4][NR], red_l[4][NR];
-    __shared__ f32x4 red_o[NRT * DT * 4 * 64];
-    __shared__ bf16x8 qs[NRT][DJ][QP][64];
+    __shared__ int s_start[kMaxFields];
+    __shared__ uint16_t act_list[kStreams][kMaxChunkTiles / kStreams];
+    __shared__ int n_act[kStreams];
+    __shared__ float xm[NR], xl[NR];
 
     const int chunk = blockIdx.x, rg = blockIdx.y, z = blockIdx.z;
     const int b = z / a.Hkv, kvh = z % a.Hkv;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int strm = wave / NRT, rt = wave % NRT;
     const int r32 = lane & 31, hh = lane >> 5;
     const int F = sm.F;
+    const int cb0 = chunk * a.CB, blk_end = min(a.NB, cb0 + a.CB);
+    const int mt0 = max(cb0, a.P >> 5);             // first tile of the chunk that reaches past the prefix
+    const int nmt = max(0, blk_end - mt0);
 
-    for (int r = tid; r < NR; r += 256) {
+    // ---- start-up: rows, per-slot visible counts, visibility words, tile lists ---
+    for (int r = tid; r < NR; r += NT) {
         const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
         row_m[r] = ri.m;
         row_head[r] = ri.head;
         row_field[r] = ri.field;
         row_off[r] = ri.off;
     }
+    for (int g = tid; g < F; g += NT) s_start[g] = sm.slot_start[g];
     __syncthreads();
-    // visible-key count of every (row, slot)
-    for (int idx = tid; idx < NR * F; idx += 256) {
+    for (int idx = tid; idx < NR * F; idx += NT) {
         const int r = idx / F, g = idx % F;
         const int f = row_field[r];
         int n = 0;
@@ -107,276 +158,271 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a, StepMeta 
         }
         vis[r][g] = (uint16_t)n;
     }
-    // query operand in LDS: fragment (rt, j) holds, per lane, row rt*32 + lane%32,
-    // d = 16*j + 8*(lane/32) + 0..7
-    for (int idx = wave; idx < NRT * DJ; idx += 4) {
-        const int rt = idx / DJ, j = idx % DJ;
+    __syncthreads();
+    for (int idx = tid; idx < nmt * NR; idx += NT) {
+        const int t = idx / NR, r = idx % NR;
+        const int key0 = (mt0 + t) * 32;
+        uint32_t bits = 0;
+        if (row_m[r] >= 0) {
+            if (key0 < a.P) {
+                const int nb = min(a.P - key0, 32);
+                bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
+            }
+            for (int g = 0; g < F; ++g) {
+                const int s0 = s_start[g];
+                if (s0 >= key0 + 32) break;        // slots are laid out in field order
+                const int lo = max(s0, key0), hi = min(s0 + (int)vis[r][g], key0 + 32);
+                if (hi > lo) {
+                    const int nb = hi - lo;
+                    bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
+                }
+            }
+        }
+        rowmask[t][r] = bits;
+    }
+    __syncthreads();
+    for (int t = wave; t < nmt; t += NT / 64) {
+        uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
+        for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
+        if (lane == 0) tile_any[t] = v;
+    }
+    __syncthreads();
+    if (wave < kStreams) {
+        // candidates of stream w: tiles cb0 + w, cb0 + w + 2, ...; keep the visible ones
+        const int blk = cb0 + wave + kStreams * lane;
+        bool actv = blk < blk_end;
+        if (actv && blk >= mt0) actv = tile_any[blk - mt0] != 0u;
+        const unsigned long long mask = __ballot(actv);
+        if (actv) act_list[wave][__popcll(mask & ((1ull << lane) - 1ull))] = (uint16_t)blk;
+        if (lane == 0) n_act[wave] = __popcll(mask);
+    }
+    __syncthreads();
+    const int n_mine = n_act[strm];
+    const int n_iter = max(n_act[0], n_act[1]);
+    // lane j keeps the j-th active tile of this stream (read back with readlane)
+    const int my_tiles = lane < n_mine ? (int)act_list[strm][lane] : 0;
+
+    // query operand in registers: row rt*32 + lane%32, d = 16*j + 8*(lane/32) + 0..7
+    Frag qh[DJ], ql[QF32 ? DJ : 1];
+    {
         const int r = rt * 32 + r32;
         const int m = row_m[r];
-        Frag fh, fl;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) fh.u[k] = fl.u[k] = 0;
-        if (m >= 0) {
-            const size_t qo = ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh;
-            if (QF32) {
-                const f32x4 q0 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo);
-                const f32x4 q1 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 4);
-                split2(q0[0], q0[1], fh.u[0], fl.u[0]);
-                split2(q0[2], q0[3], fh.u[1], fl.u[1]);
-                split2(q1[0], q1[1], fh.u[2], fl.u[2]);
-                split2(q1[2], q1[3], fh.u[3], fl.u[3]);
-            } else {
-                fh.v = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo);
+        for (int j = 0; j < DJ; ++j) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                qh[j].u[k] = 0;
+                if (QF32) ql[j].u[k] = 0;
             }
-        }
-        qs[rt][j][0][lane] = fh.v;
-        if (QF32) qs[rt][j][QP - 1][lane] = fl.v;
-    }
-    __syncthreads();
-    if (tid < F) {
-        int mx = 0;
-        for (int r = 0; r < NR; ++r) mx = max(mx, (int)vis[r][tid]);
-        maxvis[tid] = (uint16_t)mx;
-    }
-    __syncthreads();
-
-    f32x16 o[NRT][DT];
-    float m_run[NRT], l_run[NRT];
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-        m_run[rt] = kNegBig;
-        l_run[rt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[rt][dt][i] = 0.f;
-    }
-
-    const int blk_end = min(a.NB, (chunk + 1) * a.CB);
-    const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
-
-    // a tile that reaches into the slots is fetched only if some row of the row
-    // tile can see one of its keys (wave-uniform answer)
-    auto tile_active = [&](int blk) -> bool {
-        const int key0 = blk * 32;
-        if (key0 + 32 <= a.P) return true;
-        bool mine = false;
-        if (lane < 32) {
-            const int key = key0 + lane;
-            if (key < a.P) mine = true;
-            else {
-                const uint32_t tab = a.slot_tab[key - a.P];
-                mine = tab != 0xffffffffu && (tab >> 8) < maxvis[tab & 0xff];
-            }
-        }
-        return __any(mine);
-    };
-    auto load_tile = [&](int blk, bf16x8 (&kf)[DJ], bf16x8 (&vf)[DT][2]) {
-        const uint16_t* kt = a.kc + (tile_base + blk) * (32 * D);
-        const uint16_t* vt = a.vc + (tile_base + blk) * (32 * D);
-#pragma unroll
-        for (int j = 0; j < DJ; ++j)
-            kf[j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(kt + (j * 64 + lane) * 8));
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-                vf[dt][s] = __builtin_nontemporal_load(
-                    reinterpret_cast<const bf16x8*>(vt + ((dt * 2 + s) * 64 + lane) * 8));
-    };
-
-    int blk = chunk * a.CB + wave;
-    while (blk < blk_end && !tile_active(blk)) blk += 4;
-    bf16x8 kn[DJ], vn[DT][2];
-    if (blk < blk_end) load_tile(blk, kn, vn);
-
-    while (blk < blk_end) {
-        // keeps the query fragments in LDS (re-read per tile) instead of letting
-        // the compiler hoist them into 64-128 registers for the whole loop
-        asm volatile("" ::: "memory");
-        bf16x8 kf[DJ], vf[DT][2];
-#pragma unroll
-        for (int j = 0; j < DJ; ++j) kf[j] = kn[j];
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            vf[dt][0] = vn[dt][0];
-            vf[dt][1] = vn[dt][1];
-        }
-        // next tile of this wavefront: issue its loads before computing on this one
-        int nxt = blk + 4;
-        while (nxt < blk_end && !tile_active(nxt)) nxt += 4;
-        if (nxt < blk_end) load_tile(nxt, kn, vn);
-
-        const int key0 = blk * 32;
-        const bool masked = key0 + 32 > a.P;          // tile reaches into the slots
-        // register i of this lane belongs to key0 + 8*(i/4) + 4*hh + i%4.  For a
-        // tile that reaches into the slots look the keys up once: tabs[i] =
-        // field | offset << 8, anybits = keys some row of the tile can see.  Keys
-        // nobody sees may be padding or not yet written: they may hold anything.
-        uint32_t tabs[16];
-        uint32_t anybits = 0xffffu;
-        if (masked) {
-            anybits = 0;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = key0 + 8 * (i >> 2) + 4 * hh + (i & 3);
-                bool v;
-                if (key < a.P) {
-                    tabs[i] = 0xfffffffeu;            // prefix key
-                    v = true;
+            if (m >= 0) {
+                const size_t qo = ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh;
+                if (QF32) {
+                    const f32x4 q0 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo);
+                    const f32x4 q1 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 4);
+                    split2(q0[0], q0[1], qh[j].u[0], ql[j].u[0]);
+                    split2(q0[2], q0[3], qh[j].u[1], ql[j].u[1]);
+                    split2(q1[0], q1[1], qh[j].u[2], ql[j].u[2]);
+                    split2(q1[2], q1[3], qh[j].u[3], ql[j].u[3]);
                 } else {
-                    tabs[i] = a.slot_tab[key - a.P];
-                    v = tabs[i] != 0xffffffffu && (tabs[i] >> 8) < maxvis[tabs[i] & 0xff];
-                }
-                anybits |= (v ? 1u : 0u) << i;
-            }
-            if (anybits != 0xffffu) {
-                // zero the V columns of keys nobody sees (0 * garbage must stay 0)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    uint32_t wm[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        wm[k] = ((anybits >> (8 * s + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
-                                ((anybits >> (8 * s + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        Frag cv;
-                        cv.v = vf[dt][s];
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) cv.u[k] &= wm[k];
-                        vf[dt][s] = cv.v;
-                    }
+                    qh[j].v = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo);
                 }
             }
         }
+    }
+    // the query loads above must not be counted among the tile loads below
+    __builtin_amdgcn_s_waitcnt(0);
+
+    f32x16 o[DT];
+    float m_run = kNegBig, l_run = 0.f;
 #pragma unroll
-        for (int rt = 0; rt < NRT; ++rt) {
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+
+    const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
+    // Tile i of this stream -> stage i % 3.  The K half and the V half are LPT
+    // pieces of 1 KiB; wavefront rt of the stream copies pieces rt*LPW .. +LPW.
+    const uint32_t stage_off = lds_off(&stage[strm][0][0]);
+    const uint32_t rowmask_off = lds_off(&rowmask[0][rt * 32 + r32]);
+    const uint32_t any_off = lds_off(&tile_any[0]);
+    auto issue = [&](int i, int stg) {
+        if (i >= n_mine) return;
+        const int blk = __builtin_amdgcn_readlane(my_tiles, i);
+#pragma unroll
+        for (int p = 0; p < LPW; ++p) {
+            const int piece = rt * LPW + p;                 // < DJ: K, else V
+            const uint16_t* src = (piece < DJ ? a.kc : a.vc) + (tile_base + blk) * TILE +
+                                  (piece % DJ) * 512 + lane * 8;
+            uint16_t* dst = &stage[strm][stg][piece * 512];
+            __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)dst, 16, 0, 0);
+        }
+    };
+    issue(0, 0);
+    issue(1, 1);
+
+    int stg = 0;
+    for (int i = 0; i < n_iter; ++i) {
+        // my copies of tile i have landed (those of tile i+1 may still be in flight)
+        if (i + 1 < n_mine) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // everyone's copies of tile i landed; everyone is done with tile i-1
+        asm volatile("s_barrier" ::: "memory");
+        issue(i + 2, stg == 0 ? 2 : stg - 1);
+        if (i < n_mine) {
+            const uint32_t ks = stage_off + stg * (4 * TILE) + lane * 16;      // bytes
+            const uint32_t vs = ks + 2 * TILE;
+            const int blk = __builtin_amdgcn_readlane(my_tiles, i);
+            const bool masked = blk >= mt0;
+            uint32_t vbits = 0xffffu, anyb = 0xffffu;
+            if (masked) {
+                uint32_t w0 = lds_read32(rowmask_off + (blk - mt0) * (NR * 4));
+                uint32_t w1 = lds_read32(any_off + (blk - mt0) * 4);
+                // the registers are operands of the wait so that nothing that uses
+                // them can be scheduled ahead of it
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w0), "+v"(w1)::"memory");
+                vbits = lane_bits(w0, hh);
+                anyb = lane_bits(w1, hh);
+            }
+            Frag kf[DJ];
+#pragma unroll
+            for (int j = 0; j < DJ; ++j) lds_read128(kf[j], ks + j * 1024);
             f32x16 sc;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+            for (int k = 0; k < 16; ++k) sc[k] = 0.f;
+            // scalar loads share the counter and may return out of order, so only
+            // a full drain is a safe wait
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int j = 0; j < DJ; ++j) {
-                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qs[rt][j][0][lane], sc, 0, 0, 0);
-                if (QF32)
-                    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qs[rt][j][QP - 1][lane], sc, 0, 0, 0);
+                // tie the register to the wait so that the matrix instruction
+                // cannot be scheduled before it
+                asm volatile("" : "+v"(kf[j].v));
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qh[j].v, sc, 0, 0, 0);
+                if (QF32) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, ql[j].v, sc, 0, 0, 0);
             }
-            uint32_t vbits = 0xffffu;
-            if (masked) {
-                vbits = 0;
-                const int r = rt * 32 + r32;
-                const bool act = row_m[r] >= 0;
+            // V fragments: requested now, consumed after the softmax
+            Frag vf[DT][2];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const uint32_t tab = tabs[i];
-                    const bool v = tab == 0xfffffffeu ? act
-                                 : (tab != 0xffffffffu && (tab >> 8) < vis[r][tab & 0xff]);
-                    vbits |= (v ? 1u : 0u) << i;
-                }
-            }
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) lds_read128(vf[dt][s], vs + (dt * 2 + s) * 1024);
             float mx = kNegBig;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                sc[i] = (vbits >> i & 1u) ? sc[i] * a.scale_log2 : kNegBig;
-                mx = fmaxf(mx, sc[i]);
+            for (int k = 0; k < 16; ++k) {
+                sc[k] = (vbits >> k & 1u) ? sc[k] * a.scale_log2 : kNegBig;
+                mx = fmaxf(mx, sc[k]);
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[rt], mx);
-            const float alpha = exp2f(m_run[rt] - m_new);
-            m_run[rt] = m_new;
+            mx = fmaxf(mx, other_half(mx, hh));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
             float psum = 0.f;
             float p[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                p[i] = (vbits >> i & 1u) ? exp2f(sc[i] - m_new) : 0.f;
-                psum += p[i];
+            for (int k = 0; k < 16; ++k) {
+                p[k] = (vbits >> k & 1u) ? __builtin_amdgcn_exp2f(sc[k] - m_new) : 0.f;
+                psum += p[k];
             }
-            l_run[rt] = l_run[rt] * alpha + psum;
+            l_run = l_run * alpha + psum;
             Frag ph[2], pl[2];
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
                     split2(p[8 * s + 2 * k], p[8 * s + 2 * k + 1], ph[s].u[k], pl[s].u[k]);
-            const bool rescale = __any(alpha != 1.0f);
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                if (rescale) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[rt][dt][i] *= alpha;
-                }
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    o[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], ph[s].v, o[rt][dt], 0, 0, 0);
-                    o[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], pl[s].v, o[rt][dt], 0, 0, 0);
-                }
-            }
-        }
-        blk = nxt;
-    }
-
-    // ---- merge the four wavefronts (fixed order), emit one partial ---------------
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-        l_run[rt] += __shfl_xor(l_run[rt], 32);
-        if (hh == 0) red_m[wave][rt * 32 + r32] = m_run[rt];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-        const int r = rt * 32 + r32;
-        const float mg = fmaxf(fmaxf(red_m[0][r], red_m[1][r]), fmaxf(red_m[2][r], red_m[3][r]));
-        const float sc = exp2f(m_run[rt] - mg);
-        if (hh == 0) red_l[wave][r] = l_run[rt] * sc;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[rt][dt][i] *= sc;
-    }
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int rt = 0; rt < NRT; ++rt)
+            if (__any(alpha != 1.0f)) {
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) {
-                        f32x4 v = {o[rt][dt][4 * i4], o[rt][dt][4 * i4 + 1], o[rt][dt][4 * i4 + 2],
-                                   o[rt][dt][4 * i4 + 3]};
-                        const int idx = ((rt * DT + dt) * 4 + i4) * 64 + lane;
-                        if (w == 0) red_o[idx] = v;
-                        else red_o[idx] += v;
+                    for (int k = 0; k < 16; ++k) o[dt][k] *= alpha;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) asm volatile("" : "+v"(vf[dt][s].v));
+            if (masked) {
+                // keys nobody sees may be padding or not yet written: whatever the
+                // cache holds there is zeroed so that 0 * garbage stays 0
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t wm = ((anyb >> (8 * s + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
+                                            ((anyb >> (8 * s + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt) vf[dt][s].u[k] &= wm;
                     }
+            }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, ph[s].v, o[dt], 0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, pl[s].v, o[dt], 0, 0, 0);
+                }
         }
-        __syncthreads();
+        stg = stg == kStages - 1 ? 0 : stg + 1;
     }
-    const size_t pidx = ((size_t)z * a.n_rg + rg) * a.n_chunks + chunk;
-    f32x4* po = reinterpret_cast<f32x4*>(a.part_o) + pidx * (NRT * DT * 4 * 64);
-    for (int i = tid; i < NRT * DT * 4 * 64; i += 256) po[i] = red_o[i];
-    if (tid < NR) {
-        float* ml = a.part_ml + (pidx * NR + tid) * 2;
-        ml[0] = fmaxf(fmaxf(red_m[0][tid], red_m[1][tid]), fmaxf(red_m[2][tid], red_m[3][tid]));
-        ml[1] = red_l[0][tid] + red_l[1][tid] + red_l[2][tid] + red_l[3][tid];
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+
+    // ---- fold stream 1 into stream 0 through LDS, emit the chunk's partial ---------
+    l_run += other_half(l_run, hh);
+    __syncthreads();                                   // all tiles consumed: the ring is free
+    f32x4* xo = reinterpret_cast<f32x4*>(&stage[0][0][0]);   // NRT * DT * 4 * 64 vectors
+    if (strm == 1) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4)
+                xo[((rt * DT + dt) * 4 + i4) * 64 + lane] =
+                    f32x4{o[dt][4 * i4], o[dt][4 * i4 + 1], o[dt][4 * i4 + 2], o[dt][4 * i4 + 3]};
+        if (hh == 0) {
+            xm[rt * 32 + r32] = m_run;
+            xl[rt * 32 + r32] = l_run;
+        }
+    }
+    __syncthreads();
+    if (strm == 0) {
+        const int r = rt * 32 + r32;
+        const float m1 = xm[r], l1 = xl[r];
+        const float mg = fmaxf(m_run, m1);
+        const float e0 = __builtin_amdgcn_exp2f(m_run - mg), e1 = __builtin_amdgcn_exp2f(m1 - mg);
+        const size_t pidx = ((size_t)z * a.n_rg + rg) * a.n_chunks + chunk;
+        f32x4* po = reinterpret_cast<f32x4*>(a.part_o) + pidx * (NRT * DT * 4 * 64);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int idx = ((rt * DT + dt) * 4 + i4) * 64 + lane;
+                const f32x4 mine = {o[dt][4 * i4], o[dt][4 * i4 + 1], o[dt][4 * i4 + 2], o[dt][4 * i4 + 3]};
+                po[idx] = mine * e0 + xo[idx] * e1;
+            }
+        if (hh == 0) {
+            float* ml = a.part_ml + (pidx * NR + r) * 2;
+            ml[0] = mg;
+            ml[1] = l_run * e0 + l1 * e1;
+        }
     }
 }
 
-// Merge the chunks' partials of one (scene, kv head, row group) in chunk order.
-// One thread per 4 consecutive head-dim elements of one row.
+// Merge the chunks' partials of one row of one (scene, kv head, row group).
+// One workgroup per row: D/4 column quads x 8 chunk groups; each thread folds
+// the chunks c = cg, cg + 8, ... and the groups meet in LDS in a fixed order.
 template <int D, int NRT>
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm) {
-    constexpr int DT = D / 32, NR = NRT * 32, Q4 = NRT * DT * 4 * 64;
-    const int q4 = blockIdx.x * 256 + threadIdx.x;
-    if (q4 >= Q4) return;
-    const int zr = blockIdx.y, z = zr / a.n_rg, rg = zr % a.n_rg;
+__global__ __launch_bounds__(D * 2) void attn_merge_kernel(AttnArgs a, StepMeta sm) {
+    constexpr int DT = D / 32, NR = NRT * 32, Q4 = NRT * DT * 4 * 64, NQ = D / 4, NG = 8;
+    __shared__ f32x4 racc[NG][NQ];
+    __shared__ float rl[NG][NQ];
+    const int r = blockIdx.x, zr = blockIdx.y, z = zr / a.n_rg, rg = zr % a.n_rg;
     const int b = z / a.Hkv, kvh = z % a.Hkv;
-    const int lane = q4 & 63, i4 = (q4 >> 6) & 3, dt = (q4 >> 8) % DT, rt = (q4 >> 8) / DT;
-    const int r = rt * 32 + (lane & 31);
-    const int d0 = 32 * dt + 8 * i4 + 4 * (lane >> 5);
+    const int qd = threadIdx.x % NQ, cg = threadIdx.x / NQ;
+    const int d0 = 4 * qd;
     const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
     if (ri.m < 0) {
         // rows of inactive branches: zero in the fp32 output, nothing for fragments
         const int gr = rg * NR + r, jr = gr / a.G, ridx = jr / sm.T;
-        if (a.out_f32 && ridx < sm.R) {
+        if (a.out_f32 && ridx < sm.R && cg == 0) {
             const int m = (b * sm.R + ridx) * sm.T + jr % sm.T;
             const int head = kvh * a.G + gr % a.G;
             *reinterpret_cast<f32x4*>(a.out_f32 + ((size_t)m * a.Hq + head) * D + d0) =
@@ -384,48 +430,51 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm
         }
         return;
     }
+    // position of (row r, columns d0..d0+3) in the partial's accumulator order
+    const int rt = r >> 5, dt = d0 >> 5, i4 = (d0 & 31) >> 3, hh = (d0 & 7) >> 2;
+    const int q4 = ((rt * DT + dt) * 4 + i4) * 64 + (r & 31) + 32 * hh;
     const size_t p0 = (size_t)zr * a.n_chunks;
     float mg = kNegBig;
     for (int c = 0; c < a.n_chunks; ++c) mg = fmaxf(mg, a.part_ml[((p0 + c) * NR + r) * 2]);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float L = 0.f;
-    for (int c = 0; c < a.n_chunks; ++c) {
+    for (int c = cg; c < a.n_chunks; c += NG) {
         const float* ml = a.part_ml + ((p0 + c) * NR + r) * 2;
         const float l = ml[1];
         if (l > 0.f) {
-            const float w = exp2f(ml[0] - mg);
+            const float w = __builtin_amdgcn_exp2f(ml[0] - mg);
             L += w * l;
             acc += w * reinterpret_cast<const f32x4*>(a.part_o)[(p0 + c) * Q4 + q4];
         }
     }
-    const float inv = L > 0.f ? 1.0f / L : 0.f;
-    acc *= inv;
+    racc[cg][qd] = acc;
+    rl[cg][qd] = L;
+    __syncthreads();
+    if (cg != 0) return;
+    for (int g = 1; g < NG; ++g) {
+        acc += racc[g][qd];
+        L += rl[g][qd];
+    }
+    acc *= L > 0.f ? 1.0f / L : 0.f;
     if (a.out_f32) {
         *reinterpret_cast<f32x4*>(a.out_f32 + ((size_t)ri.m * a.Hq + ri.head) * D + d0) = acc;
     } else {
-        uint16_t hi[4], lo[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) split_bf16(acc[i], hi[i], lo[i]);
+        uint32_t hi[2], lo[2];
+        split2(acc[0], acc[1], hi[0], lo[0]);
+        split2(acc[2], acc[3], hi[1], lo[1]);
         const size_t o = act_frag_index(ri.m, ri.head * D + d0, a.Hq * D / 32);
-        *reinterpret_cast<uint2*>(a.out_hi + o) =
-            make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
-        *reinterpret_cast<uint2*>(a.out_lo + o) =
-            make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+        *reinterpret_cast<uint2*>(a.out_hi + o) = make_uint2(hi[0], hi[1]);
+        *reinterpret_cast<uint2*>(a.out_lo + o) = make_uint2(lo[0], lo[1]);
     }
 }
 
 template <int D, int NRT>
 void launch_t(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
     const int z = sm.B * a.Hkv;
-    if (a.q_f32)
-        hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), dim3(a.n_chunks, a.n_rg, z), dim3(256),
-                           0, st, a, sm);
-    else
-        hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), dim3(a.n_chunks, a.n_rg, z), dim3(256),
-                           0, st, a, sm);
-    constexpr int Q4 = NRT * (D / 32) * 4 * 64;
-    hipLaunchKernelGGL((attn_merge_kernel<D, NRT>), dim3((Q4 + 255) / 256, z * a.n_rg), dim3(256), 0,
-                       st, a, sm);
+    const dim3 grid(a.n_chunks, a.n_rg, z), block(kStreams * NRT * 64);
+    if (a.q_f32) hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), grid, block, 0, st, a, sm);
+    else hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), grid, block, 0, st, a, sm);
+    hipLaunchKernelGGL((attn_merge_kernel<D, NRT>), dim3(NRT * 32, z * a.n_rg), dim3(D * 2), 0, st, a, sm);
 }
 
 }  // namespace

@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -104,13 +105,18 @@ void plan_attention(fdc_ctx* c) {
     c->attn_nrt = rows > 32 ? 2 : 1;
     const int NR = c->attn_nrt * 32;
     c->attn_rg_max = (rows + NR - 1) / NR;
-    // enough workgroups to cover the chip a few times, at least one 32-key tile
-    // per wavefront
+    // One workgroup per compute unit is resident at head_dim 128 (the K/V ring
+    // takes most of LDS), two at 64: aim at that many workgroups in total, at
+    // least two tiles per stream, within the kernel's per-chunk limits.
     const long zr = (long)c->B * c->m.n_kv_heads * c->attn_rg_max;
-    const long want_wgs = 768;
-    long chunks = std::max(1L, want_wgs / zr);
+    long want_wgs = 256L * (c->m.head_dim == 128 ? 1 : 2);
+    if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
+    long chunks = std::max(1L, (want_wgs + zr / 2) / zr);
     long cb = (c->NB + chunks - 1) / chunks;
-    cb = std::max(4L, (cb + 3) / 4 * 4);
+    cb = std::max(4L, (cb + 1) / 2 * 2);
+    cb = std::min(cb, (long)kMaxChunkTiles);
+    const long masked_total = c->NB - c->P / 32;
+    if (masked_total > kMaxMaskedTiles) cb = std::min(cb, (long)kMaxMaskedTiles);
     c->attn_cb = (int)cb;
     c->attn_chunks = (int)((c->NB + cb - 1) / cb);
 }
