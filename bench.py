@@ -291,6 +291,7 @@ def main():
     ap.add_argument("--dag-seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
+    ap.add_argument("--single", action="store_true", help="cfg3: only --rho, no sweep over densities")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -303,8 +304,8 @@ def main():
     from paper_2602_02864_amd import lib
     lib()                                            # fails loudly if the library is not built
     if args.workload == "cfg3":
-        sweep = [run_attention(args, rho) for rho in (0.0, 0.1, 0.3, 1.0)]
-        main_r = [r for r in sweep if f"rho={args.rho}," in r["workload"]] or [sweep[2]]
+        sweep = [run_attention(args, rho) for rho in ((args.rho,) if args.single else (0.0, 0.1, 0.3, 1.0))]
+        main_r = [r for r in sweep if f"rho={args.rho}," in r["workload"]] or [sweep[-1]]
         a = main_r[0]
         res = {"metric": "masked-attention HBM GB/s", "value": a["achieved"], "unit": "GB/s", "n_gpus": 1,
                "steps": a["launches"], "warmup": max(3, args.warmup), "ms_per_step": a["avg_us"] / 1e3,

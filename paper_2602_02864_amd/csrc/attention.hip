@@ -12,8 +12,8 @@
 // Inside a workgroup two independent tile streams run side by side (even / odd
 // active tiles of the chunk).  A stream is NRT wavefronts, one per 32-row tile;
 // they share each 32-key K/V tile through LDS.  Tiles are copied HBM -> LDS
-// with the direct-to-LDS load (no registers involved) into a three-stage ring,
-// so two tiles per stream are always in flight while a third is consumed.  The
+// with the direct-to-LDS load (no registers involved) into a four-stage ring,
+// so three tiles per stream are in flight while a fourth is consumed.  The
 // cache stores tiles in matrix-operand order, so one load instruction moves a
 // contiguous 1 KiB and the LDS image is read back conflict-free.
 //
@@ -30,6 +30,8 @@
 // P^T operand of O^T = V^T * P^T because the V tiles are stored in that key
 // order.  Softmax weights (and fp32 queries) enter the matrix cores as a bf16
 // head plus a bf16 tail, so the only bf16 rounding left is that of the cache.
+#include <type_traits>
+
 #include "kernels_common.hpp"
 #include "fdc_launch.hpp"
 
@@ -38,7 +40,7 @@ namespace fdc {
 namespace {
 
 constexpr float kNegBig = -1.0e30f;
-constexpr int kStages = 3;
+constexpr int kStages = 4;
 constexpr int kStreams = 2;
 
 struct RowInfo {
@@ -146,45 +148,47 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
         row_field[r] = ri.field;
         row_off[r] = ri.off;
     }
-    for (int g = tid; g < F; g += NT) s_start[g] = sm.slot_start[g];
-    __syncthreads();
-    for (int idx = tid; idx < NR * F; idx += NT) {
-        const int r = idx / F, g = idx % F;
-        const int f = row_field[r];
-        int n = 0;
-        if (f >= 0) {
-            if (g == f) n = row_off[r] + 1;
-            else if ((a.anc[f] >> g) & 1ull) n = sm.valid_len[b * F + g];
-        }
-        vis[r][g] = (uint16_t)n;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < nmt * NR; idx += NT) {
-        const int t = idx / NR, r = idx % NR;
-        const int key0 = (mt0 + t) * 32;
-        uint32_t bits = 0;
-        if (row_m[r] >= 0) {
-            if (key0 < a.P) {
-                const int nb = min(a.P - key0, 32);
-                bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
+    if (nmt > 0) {                                   // uniform: the chunk reaches into the slots
+        for (int g = tid; g < F; g += NT) s_start[g] = sm.slot_start[g];
+        __syncthreads();
+        for (int idx = tid; idx < NR * F; idx += NT) {
+            const int r = idx / F, g = idx % F;
+            const int f = row_field[r];
+            int n = 0;
+            if (f >= 0) {
+                if (g == f) n = row_off[r] + 1;
+                else if ((a.anc[f] >> g) & 1ull) n = sm.valid_len[b * F + g];
             }
-            for (int g = 0; g < F; ++g) {
-                const int s0 = s_start[g];
-                if (s0 >= key0 + 32) break;        // slots are laid out in field order
-                const int lo = max(s0, key0), hi = min(s0 + (int)vis[r][g], key0 + 32);
-                if (hi > lo) {
-                    const int nb = hi - lo;
-                    bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
+            vis[r][g] = (uint16_t)n;
+        }
+        __syncthreads();
+        for (int idx = tid; idx < nmt * NR; idx += NT) {
+            const int t = idx / NR, r = idx % NR;
+            const int key0 = (mt0 + t) * 32;
+            uint32_t bits = 0;
+            if (row_m[r] >= 0) {
+                if (key0 < a.P) {
+                    const int nb = min(a.P - key0, 32);
+                    bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
+                }
+                for (int g = 0; g < F; ++g) {
+                    const int s0 = s_start[g];
+                    if (s0 >= key0 + 32) break;        // slots are laid out in field order
+                    const int lo = max(s0, key0), hi = min(s0 + (int)vis[r][g], key0 + 32);
+                    if (hi > lo) {
+                        const int nb = hi - lo;
+                        bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
+                    }
                 }
             }
+            rowmask[t][r] = bits;
         }
-        rowmask[t][r] = bits;
-    }
-    __syncthreads();
-    for (int t = wave; t < nmt; t += NT / 64) {
-        uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
-        for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
-        if (lane == 0) tile_any[t] = v;
+        __syncthreads();
+        for (int t = wave; t < nmt; t += NT / 64) {
+            uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
+            for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
+            if (lane == 0) tile_any[t] = v;
+        }
     }
     __syncthreads();
     if (wave < kStreams) {
@@ -254,113 +258,124 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
             const uint16_t* src = (piece < DJ ? a.kc : a.vc) + (tile_base + blk) * TILE +
                                   (piece % DJ) * 512 + lane * 8;
             uint16_t* dst = &stage[strm][stg][piece * 512];
-            __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)dst, 16, 0, 2 /* nt: streamed once */);
         }
     };
-    issue(0, 0);
-    issue(1, 1);
-
-    int stg = 0;
-    for (int i = 0; i < n_iter; ++i) {
-        // my copies of tile i have landed (those of tile i+1 may still be in flight)
-        if (i + 1 < n_mine) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        // everyone's copies of tile i landed; everyone is done with tile i-1
-        asm volatile("s_barrier" ::: "memory");
-        issue(i + 2, stg == 0 ? 2 : stg - 1);
-        if (i < n_mine) {
-            const uint32_t ks = stage_off + stg * (4 * TILE) + lane * 16;      // bytes
-            const uint32_t vs = ks + 2 * TILE;
-            const int blk = __builtin_amdgcn_readlane(my_tiles, i);
-            const bool masked = blk >= mt0;
-            uint32_t vbits = 0xffffu, anyb = 0xffffu;
-            if (masked) {
-                uint32_t w0 = lds_read32(rowmask_off + (blk - mt0) * (NR * 4));
-                uint32_t w1 = lds_read32(any_off + (blk - mt0) * 4);
-                // the registers are operands of the wait so that nothing that uses
-                // them can be scheduled ahead of it
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w0), "+v"(w1)::"memory");
-                vbits = lane_bits(w0, hh);
-                anyb = lane_bits(w1, hh);
-            }
-            Frag kf[DJ];
+    // one 32-key tile against this wavefront's 32 rows; MASKED tiles reach into
+    // the slots and carry a visibility word per row
+    auto tile = [&](auto masked_tag, int stg, int blk) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const uint32_t ks = stage_off + stg * (4 * TILE) + lane * 16;      // bytes
+        const uint32_t vs = ks + 2 * TILE;
+        uint32_t vbits = 0xffffu, anyb = 0xffffu;
+        if (MASKED) {
+            uint32_t w0 = lds_read32(rowmask_off + (blk - mt0) * (NR * 4));
+            uint32_t w1 = lds_read32(any_off + (blk - mt0) * 4);
+            // the registers are operands of the wait so that nothing that uses
+            // them can be scheduled ahead of it
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w0), "+v"(w1)::"memory");
+            vbits = lane_bits(w0, hh);
+            anyb = lane_bits(w1, hh);
+        }
+        Frag kf[DJ];
 #pragma unroll
-            for (int j = 0; j < DJ; ++j) lds_read128(kf[j], ks + j * 1024);
-            f32x16 sc;
+        for (int j = 0; j < DJ; ++j) lds_read128(kf[j], ks + j * 1024);
+        f32x16 sc;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) sc[k] = 0.f;
-            // scalar loads share the counter and may return out of order, so only
-            // a full drain is a safe wait
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        for (int k = 0; k < 16; ++k) sc[k] = 0.f;
+        // scalar loads share the counter and may return out of order, so only
+        // a full drain is a safe wait
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int j = 0; j < DJ; ++j) {
-                // tie the register to the wait so that the matrix instruction
-                // cannot be scheduled before it
-                asm volatile("" : "+v"(kf[j].v));
-                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qh[j].v, sc, 0, 0, 0);
-                if (QF32) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, ql[j].v, sc, 0, 0, 0);
-            }
-            // V fragments: requested now, consumed after the softmax
-            Frag vf[DT][2];
+        for (int j = 0; j < DJ; ++j) {
+            // tie the register to the wait so that the matrix instruction
+            // cannot be scheduled before it
+            asm volatile("" : "+v"(kf[j].v));
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qh[j].v, sc, 0, 0, 0);
+            if (QF32) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, ql[j].v, sc, 0, 0, 0);
+        }
+        // V fragments: requested now, consumed after the softmax
+        Frag vf[DT][2];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) lds_read128(vf[dt][s], vs + (dt * 2 + s) * 1024);
+        // running max and sum are kept in the exponent's (log2, scaled) domain
+        float mx = kNegBig;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            if (MASKED) sc[k] = (vbits >> k & 1u) ? sc[k] : kNegBig;
+            mx = fmaxf(mx, sc[k]);
+        }
+        mx = fmaxf(mx, other_half(mx, hh));
+        const float m_new = fmaxf(m_run, mx * a.scale_log2);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+        float p[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            p[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[k], a.scale_log2, -m_new));
+            if (MASKED) p[k] = (vbits >> k & 1u) ? p[k] : 0.f;
+            psum += p[k];
+        }
+        l_run = l_run * alpha + psum;
+        Frag ph[2], pl[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                split2(p[8 * s + 2 * k], p[8 * s + 2 * k + 1], ph[s].u[k], pl[s].u[k]);
+        if (__any(alpha != 1.0f)) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int s = 0; s < 2; ++s) lds_read128(vf[dt][s], vs + (dt * 2 + s) * 1024);
-            float mx = kNegBig;
+                for (int k = 0; k < 16; ++k) o[dt][k] *= alpha;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                sc[k] = (vbits >> k & 1u) ? sc[k] * a.scale_log2 : kNegBig;
-                mx = fmaxf(mx, sc[k]);
-            }
-            mx = fmaxf(mx, other_half(mx, hh));
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
-            float psum = 0.f;
-            float p[16];
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                p[k] = (vbits >> k & 1u) ? __builtin_amdgcn_exp2f(sc[k] - m_new) : 0.f;
-                psum += p[k];
-            }
-            l_run = l_run * alpha + psum;
-            Frag ph[2], pl[2];
+            for (int s = 0; s < 2; ++s) asm volatile("" : "+v"(vf[dt][s].v));
+        if (MASKED) {
+            // keys nobody sees may be padding or not yet written: whatever the
+            // cache holds there is zeroed so that 0 * garbage stays 0
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    split2(p[8 * s + 2 * k], p[8 * s + 2 * k + 1], ph[s].u[k], pl[s].u[k]);
-            if (__any(alpha != 1.0f)) {
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t wm = ((anyb >> (8 * s + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
+                                        ((anyb >> (8 * s + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int k = 0; k < 16; ++k) o[dt][k] *= alpha;
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) asm volatile("" : "+v"(vf[dt][s].v));
-            if (masked) {
-                // keys nobody sees may be padding or not yet written: whatever the
-                // cache holds there is zeroed so that 0 * garbage stays 0
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const uint32_t wm = ((anyb >> (8 * s + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
-                                            ((anyb >> (8 * s + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
-#pragma unroll
-                        for (int dt = 0; dt < DT; ++dt) vf[dt][s].u[k] &= wm;
-                    }
-            }
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, ph[s].v, o[dt], 0, 0, 0);
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, pl[s].v, o[dt], 0, 0, 0);
+                    for (int dt = 0; dt < DT; ++dt) vf[dt][s].u[k] &= wm;
                 }
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, ph[s].v, o[dt], 0, 0, 0);
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, pl[s].v, o[dt], 0, 0, 0);
+            }
+    };
+
+#pragma unroll
+    for (int i = 0; i < kStages - 1; ++i) issue(i, i);
+
+    int stg = 0;
+    for (int i = 0; i < n_iter; ++i) {
+        // my copies of tile i have landed; up to kStages - 2 later tiles stay in flight
+        const int ahead = min(n_mine - 1 - i, kStages - 2);
+        if (ahead >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPW) : "memory");
+        else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // everyone's copies of tile i landed; everyone is done with tile i-1
+        asm volatile("s_barrier" ::: "memory");
+        issue(i + kStages - 1, stg == 0 ? kStages - 1 : stg - 1);
+        if (i < n_mine) {
+            const int blk = __builtin_amdgcn_readlane(my_tiles, i);
+            if (blk >= mt0) tile(std::true_type{}, stg, blk);
+            else tile(std::false_type{}, stg, blk);
         }
         stg = stg == kStages - 1 ? 0 : stg + 1;
     }

@@ -18,7 +18,7 @@ constexpr int kMaxFields = 64;      // one 64-bit ancestor word per field in the
 constexpr int kMaxRowsDense = 16;   // rows per step the streaming projections take
 constexpr int kStageSlots = 8;      // pinned staging ring for per-step metadata
 constexpr int kMaxChunkTiles = 128; // 32-key tiles one attention workgroup walks at most
-constexpr int kMaxMaskedTiles = 64; // ... of which this many may reach into the slots
+constexpr int kMaxMaskedTiles = 32; // ... of which this many may reach into the slots
 
 // How one projection y = x W^T is cut: S splits of the reduction dimension,
 // each handled by workgroups of `nw` wavefronts that keep their slice of the
