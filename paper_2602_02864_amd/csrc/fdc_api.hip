@@ -48,7 +48,7 @@ struct fdc_ctx {
     char* ws = nullptr;
     size_t ws_bytes = 0;
     struct Off {
-        size_t anc, slot_start, slot_tab, inv_freq, meta, x, a_hi, a_lo, o_hi, o_lo, h_hi, h_lo, q,
+        size_t anc, slot_start, slot_tab, inv_freq, rope_tab, meta, x, a_hi, a_lo, o_hi, o_lo, h_hi, h_lo, q,
             part, logits, attn_o, attn_ml, tok_tmp, end;
     } off{};
     size_t meta_ints = 0;
@@ -136,6 +136,7 @@ size_t carve(fdc_ctx* c) {
     c->off.slot_start = take(sizeof(int32_t) * c->F);
     c->off.slot_tab = take(sizeof(uint32_t) * std::max(1, c->Npad - c->P));
     c->off.inv_freq = take(sizeof(double) * (m.head_dim / 2));
+    c->off.rope_tab = take(sizeof(float2) * (size_t)c->Npad * (m.head_dim / 2));
     c->meta_ints = (size_t)2 * c->B * c->Rmax + (size_t)c->B * c->F;
     c->off.meta = take(sizeof(int32_t) * c->meta_ints);
     c->off.x = take(sizeof(float) * Mp * m.d_model);
@@ -419,6 +420,8 @@ int32_t fdc_set_workspace(fdc_ctx* c, void* ws, size_t bytes, void* stream) {
     FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.slot_start), c->slot_start.data(), sizeof(int32_t) * c->F, hipMemcpyHostToDevice, st));
     FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.slot_tab), tab.data(), sizeof(uint32_t) * tab.size(), hipMemcpyHostToDevice, st));
     FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.inv_freq), inv.data(), sizeof(double) * inv.size(), hipMemcpyHostToDevice, st));
+    launch_rope_table(c->at<double>(c->off.inv_freq), c->at<float2>(c->off.rope_tab), c->Npad, c->m.head_dim / 2, st);
+    FDC_HIP(hipGetLastError());
     FDC_HIP(hipStreamSynchronize(st));
     return FDC_OK;
 }
@@ -592,7 +595,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         ra.q = q;
         ra.kc = c->kc + (size_t)l * c->kv_layer_elems;
         ra.vc = c->vc + (size_t)l * c->kv_layer_elems;
-        ra.inv_freq = c->at<double>(c->off.inv_freq);
+        ra.tab = c->at<float2>(c->off.rope_tab);
         ra.M = M;
         ra.Hq = m.n_q_heads;
         ra.Hkv = m.n_kv_heads;

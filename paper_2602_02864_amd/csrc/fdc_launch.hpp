@@ -62,10 +62,11 @@ struct RopeArgs {
     float* q;                 // fp32 [M][Hq][D] rotated queries
     uint16_t* kc;             // layer base of the K cache
     uint16_t* vc;
-    const double* inv_freq;   // [D/2]
+    const float2* tab;        // [N][D/2] (cos, sin) of pos * base^(-2i/D)
     int M, Hq, Hkv, D, NB;    // NB = 32-key tiles per (scene, kv head)
 };
 void launch_rope_append(const RopeArgs& a, const StepMeta& sm, hipStream_t st);
+void launch_rope_table(const double* inv_freq, float2* tab, int n_pos, int half, hipStream_t st);
 
 void launch_kv_scatter(const uint16_t* k_new, const uint16_t* v_new, const int32_t* row_scene,
                        const int32_t* row_pos, int n_rows, uint16_t* kc, uint16_t* vc, int B,

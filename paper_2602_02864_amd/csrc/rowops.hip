@@ -22,42 +22,77 @@ __device__ __forceinline__ float block_sum(float v, float* sh) {
 }
 
 // One workgroup per row.  x <- (embedding | x + sum of partials); a <- rmsnorm(x) * gain.
+// Every thread owns up to kNormVec groups of four consecutive columns and issues
+// all of its loads before it touches any of them: the kernel is one round trip
+// to memory, one block reduction and one round of stores.
+constexpr int kNormVec = 5;                                  // 256 threads * 4 * 5 = d_model <= 5120
 __global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a, StepMeta sm) {
     __shared__ float sh[4];
-    extern __shared__ float row[];                         // [d]
     const int m = blockIdx.x;
     const bool active = sm.branch_field == nullptr || sm.branch_field[m / sm.T] >= 0;
-    float ss = 0.f;
-    for (int k = threadIdx.x; k < a.d; k += blockDim.x) {
-        float v = 0.f;
-        if (active) {
-            if (a.tok) {
-                int t = a.tok[m];
-                t = t < 0 ? 0 : (t >= a.vocab ? a.vocab - 1 : t);
-                v = bf2f(a.emb[(size_t)t * a.d + k]);
-            } else if (a.emb_rows) {
-                v = bf2f(a.emb_rows[(size_t)m * a.d + k]);
+    const int nvec = a.d >> 2;
+    f32x4 v[kNormVec];
+    const float* __restrict__ xin = a.x + (size_t)m * a.d;
+    const float* __restrict__ part = a.part;
+    const uint16_t* __restrict__ erow = nullptr;
+    if (a.tok) {
+        int t = active ? a.tok[m] : 0;
+        t = t < 0 ? 0 : (t >= a.vocab ? a.vocab - 1 : t);
+        erow = a.emb + (size_t)t * a.d;
+    } else if (a.emb_rows) {
+        erow = a.emb_rows + (size_t)m * a.d;
+    }
+#pragma unroll
+    for (int i = 0; i < kNormVec; ++i) {
+        const int q = threadIdx.x + i * 256;
+        v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (q < nvec && active) {
+            if (erow) {
+                const uint2 e = *reinterpret_cast<const uint2*>(erow + 4 * q);
+                v[i] = f32x4{__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xffff0000u),
+                             __uint_as_float(e.y << 16), __uint_as_float(e.y & 0xffff0000u)};
             } else {
-                v = a.x[(size_t)m * a.d + k];
-                for (int s = 0; s < a.S; ++s) v += a.part[((size_t)s * a.M + m) * a.d + k];
+                v[i] = *reinterpret_cast<const f32x4*>(xin + 4 * q);
             }
         }
-        row[k] = v;
-        ss += v * v;
-        a.x[(size_t)m * a.d + k] = v;
-        if (a.hidden_x) a.hidden_x[(size_t)m * a.d + k] = v;
     }
+    if (!erow && active) {
+        for (int s = 0; s < a.S; ++s) {
+            f32x4 p[kNormVec];
+#pragma unroll
+            for (int i = 0; i < kNormVec; ++i) {
+                const int q = threadIdx.x + i * 256;
+                p[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (q < nvec) p[i] = *reinterpret_cast<const f32x4*>(part + ((size_t)s * a.M + m) * a.d + 4 * q);
+            }
+#pragma unroll
+            for (int i = 0; i < kNormVec; ++i) v[i] += p[i];
+        }
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormVec; ++i) ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
     const float tot = block_sum(ss, sh);
     const float rstd = rsqrtf(tot / (float)a.d + a.eps);
     const int KT = a.d >> 5;
-    for (int k = threadIdx.x; k < a.d; k += blockDim.x) {
-        const float n = row[k] * rstd * a.gain[k];
-        uint16_t hi, lo;
-        split_bf16(n, hi, lo);
-        const size_t o = act_frag_index(m, k, KT);
-        a.a_hi[o] = hi;
-        a.a_lo[o] = lo;
-        if (a.hidden_n) a.hidden_n[(size_t)m * a.d + k] = n;
+#pragma unroll
+    for (int i = 0; i < kNormVec; ++i) {
+        const int q = threadIdx.x + i * 256;
+        if (q >= nvec) continue;
+        const int k = 4 * q;
+        *reinterpret_cast<f32x4*>(a.x + (size_t)m * a.d + k) = v[i];
+        if (a.hidden_x) *reinterpret_cast<f32x4*>(a.hidden_x + (size_t)m * a.d + k) = v[i];
+        const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + k);
+        const f32x4 n = v[i] * rstd * g;
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) split_bf16(n[j], hi[j], lo[j]);
+        const size_t o = act_frag_index(m, k, KT);           // 4 consecutive k share a fragment lane
+        *reinterpret_cast<uint2*>(a.a_hi + o) =
+            make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
+        *reinterpret_cast<uint2*>(a.a_lo + o) =
+            make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+        if (a.hidden_n) *reinterpret_cast<f32x4*>(a.hidden_n + (size_t)m * a.d + k) = n;
     }
 }
 
@@ -69,32 +104,46 @@ __device__ __forceinline__ void cache_store(uint16_t* kc, uint16_t* vc, int scen
     else vc[tile * (32 * D) + v_tile_index<D>(pos & 31, d)] = val;
 }
 
-// One workgroup per row: sum the QKV partials, rotate q and k by the row's
-// position id (slot_start[field] + offset: fixed by the template, Sec. 3.3),
-// store q (fp32) and append k, v (bf16) to the cache at index = position id.
+// cos / sin of pos * base^(-2i/D) for every cache position, computed once in
+// double precision (the positions are fixed by the template, Sec. 3.3)
+__global__ void rope_table_kernel(const double* __restrict__ inv_freq, float2* __restrict__ tab,
+                                  int n_pos, int half) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_pos * half) return;
+    double sn, cs;
+    sincos((double)(idx / half) * inv_freq[idx % half], &sn, &cs);
+    tab[idx] = make_float2((float)cs, (float)sn);
+}
+
+// Workgroups of 256 threads, several per row: sum the QKV partials, rotate q and
+// k by the row's position id (slot_start[field] + offset: fixed by the template,
+// Sec. 3.3), store q (fp32) and append k, v (bf16) to the cache at index =
+// position id.  A thread handles one rotation pair (or two V elements); its loads
+// are independent of each other.
 template <int D>
 __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta sm) {
-    const int m = blockIdx.x;
+    const int m = blockIdx.y;
     const int br = m / sm.T, t = m % sm.T;
     const int f = sm.branch_field[br];
     if (f < 0) return;
     const int scene = br / sm.R;
     const int pos = sm.slot_start[f] + sm.branch_off[br] + t;
     const int Nqkv = (a.Hq + 2 * a.Hkv) * D;
-    const int half = D / 2;
+    constexpr int half = D / 2;
     const int n_pairs = (a.Hq + a.Hkv) * half;
-    for (int p = threadIdx.x; p < n_pairs; p += blockDim.x) {
-        const int hd = p / half, i = p % half;
+    const int n_v2 = a.Hkv * D / 2;
+    const int item = blockIdx.x * 256 + threadIdx.x;
+    const float* __restrict__ part = a.part + (size_t)m * Nqkv;
+    const size_t sstride = (size_t)a.M * Nqkv;
+    if (item < n_pairs) {
+        const int hd = item / half, i = item % half;
         float x1 = 0.f, x2 = 0.f;
         for (int s = 0; s < a.S; ++s) {
-            const float* r = a.part + ((size_t)s * a.M + m) * Nqkv + hd * D;
-            x1 += r[i];
-            x2 += r[i + half];
+            x1 += part[s * sstride + hd * D + i];
+            x2 += part[s * sstride + hd * D + i + half];
         }
-        double sn, cs;
-        sincos((double)pos * a.inv_freq[i], &sn, &cs);
-        const float c = (float)cs, sf = (float)sn;
-        const float y1 = x1 * c - x2 * sf, y2 = x2 * c + x1 * sf;
+        const float2 cssn = a.tab[(size_t)pos * half + i];
+        const float y1 = x1 * cssn.x - x2 * cssn.y, y2 = x2 * cssn.x + x1 * cssn.y;
         if (hd < a.Hq) {
             float* q = a.q + ((size_t)m * a.Hq + hd) * D;
             q[i] = y1;
@@ -104,12 +153,16 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta s
             cache_store<D>(a.kc, a.vc, scene, kvh, a.Hkv, a.NB, pos, i, true, f2bf(y1));
             cache_store<D>(a.kc, a.vc, scene, kvh, a.Hkv, a.NB, pos, i + half, true, f2bf(y2));
         }
-    }
-    const int voff = (a.Hq + a.Hkv) * D;
-    for (int e = threadIdx.x; e < a.Hkv * D; e += blockDim.x) {
-        float v = 0.f;
-        for (int s = 0; s < a.S; ++s) v += a.part[((size_t)s * a.M + m) * Nqkv + voff + e];
-        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D, false, f2bf(v));
+    } else if (item < n_pairs + n_v2) {
+        const int e = 2 * (item - n_pairs);
+        const int voff = (a.Hq + a.Hkv) * D;
+        float v0 = 0.f, v1 = 0.f;
+        for (int s = 0; s < a.S; ++s) {
+            v0 += part[s * sstride + voff + e];
+            v1 += part[s * sstride + voff + e + 1];
+        }
+        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D, false, f2bf(v0));
+        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D + 1, false, f2bf(v1));
     }
 }
 
@@ -185,12 +238,19 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
 }  // namespace
 
 void launch_resid_norm(const NormArgs& a, const StepMeta& sm, hipStream_t st) {
-    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.M), dim3(256), a.d * sizeof(float), st, a, sm);
+    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.M), dim3(256), 0, st, a, sm);
+}
+
+void launch_rope_table(const double* inv_freq, float2* tab, int n_pos, int half, hipStream_t st) {
+    const int n = n_pos * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, inv_freq, tab, n_pos, half);
 }
 
 void launch_rope_append(const RopeArgs& a, const StepMeta& sm, hipStream_t st) {
-    if (a.D == 128) hipLaunchKernelGGL(rope_append_kernel<128>, dim3(a.M), dim3(256), 0, st, a, sm);
-    else hipLaunchKernelGGL(rope_append_kernel<64>, dim3(a.M), dim3(256), 0, st, a, sm);
+    const int items = (a.Hq + a.Hkv) * a.D / 2 + a.Hkv * a.D / 2;
+    const dim3 grid((items + 255) / 256, a.M);
+    if (a.D == 128) hipLaunchKernelGGL(rope_append_kernel<128>, grid, dim3(256), 0, st, a, sm);
+    else hipLaunchKernelGGL(rope_append_kernel<64>, grid, dim3(256), 0, st, a, sm);
 }
 
 void launch_kv_scatter(const uint16_t* k_new, const uint16_t* v_new, const int32_t* row_scene,
