@@ -421,23 +421,25 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     }
 }
 
-// Merge the chunks' partials of one row of one (scene, kv head, row group).
-// One workgroup per row: D/4 column quads x 8 chunk groups; each thread folds
-// the chunks c = cg, cg + 8, ... and the groups meet in LDS in a fixed order.
-template <int D, int NRT>
-__global__ __launch_bounds__(D * 2) void attn_merge_kernel(AttnArgs a, StepMeta sm) {
-    constexpr int DT = D / 32, NR = NRT * 32, Q4 = NRT * DT * 4 * 64, NQ = D / 4, NG = 8;
-    __shared__ f32x4 racc[NG][NQ];
-    __shared__ float rl[NG][NQ];
-    const int r = blockIdx.x, zr = blockIdx.y, z = zr / a.n_rg, rg = zr % a.n_rg;
+// Merge the chunks' partials of one (scene, kv head, row group) in chunk order.
+// One thread per accumulator quad (4 consecutive head-dim elements of one row) in
+// the partial's own order, so reads are contiguous; chunks are fetched four at a
+// time (CB independent loads per thread) and folded with a running maximum.
+template <int D, int NRT, int CB>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm) {
+    constexpr int DT = D / 32, NR = NRT * 32, Q4 = NRT * DT * 4 * 64;
+    const int q4 = blockIdx.x * 256 + threadIdx.x;
+    if (q4 >= Q4) return;
+    const int zr = blockIdx.y, z = zr / a.n_rg, rg = zr % a.n_rg;
     const int b = z / a.Hkv, kvh = z % a.Hkv;
-    const int qd = threadIdx.x % NQ, cg = threadIdx.x / NQ;
-    const int d0 = 4 * qd;
+    const int lane = q4 & 63, i4 = (q4 >> 6) & 3, dt = (q4 >> 8) % DT, rt = (q4 >> 8) / DT;
+    const int r = rt * 32 + (lane & 31);
+    const int d0 = 32 * dt + 8 * i4 + 4 * (lane >> 5);
     const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
     if (ri.m < 0) {
         // rows of inactive branches: zero in the fp32 output, nothing for fragments
         const int gr = rg * NR + r, jr = gr / a.G, ridx = jr / sm.T;
-        if (a.out_f32 && ridx < sm.R && cg == 0) {
+        if (a.out_f32 && ridx < sm.R) {
             const int m = (b * sm.R + ridx) * sm.T + jr % sm.T;
             const int head = kvh * a.G + gr % a.G;
             *reinterpret_cast<f32x4*>(a.out_f32 + ((size_t)m * a.Hq + head) * D + d0) =
@@ -445,30 +447,29 @@ __global__ __launch_bounds__(D * 2) void attn_merge_kernel(AttnArgs a, StepMeta 
         }
         return;
     }
-    // position of (row r, columns d0..d0+3) in the partial's accumulator order
-    const int rt = r >> 5, dt = d0 >> 5, i4 = (d0 & 31) >> 3, hh = (d0 & 7) >> 2;
-    const int q4 = ((rt * DT + dt) * 4 + i4) * 64 + (r & 31) + 32 * hh;
     const size_t p0 = (size_t)zr * a.n_chunks;
-    float mg = kNegBig;
-    for (int c = 0; c < a.n_chunks; ++c) mg = fmaxf(mg, a.part_ml[((p0 + c) * NR + r) * 2]);
+    const f32x4* __restrict__ po = reinterpret_cast<const f32x4*>(a.part_o) + p0 * Q4 + q4;
+    const float2* __restrict__ pml = reinterpret_cast<const float2*>(a.part_ml) + p0 * NR + r;
+    float mg = kNegBig, L = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float L = 0.f;
-    for (int c = cg; c < a.n_chunks; c += NG) {
-        const float* ml = a.part_ml + ((p0 + c) * NR + r) * 2;
-        const float l = ml[1];
-        if (l > 0.f) {
-            const float w = __builtin_amdgcn_exp2f(ml[0] - mg);
-            L += w * l;
-            acc += w * reinterpret_cast<const f32x4*>(a.part_o)[(p0 + c) * Q4 + q4];
+    for (int c0 = 0; c0 < a.n_chunks; c0 += CB) {
+        float2 ml[CB];
+        f32x4 o[CB];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const int c = min(c0 + j, a.n_chunks - 1);
+            ml[j] = pml[(size_t)c * NR];
+            o[j] = po[(size_t)c * Q4];
         }
-    }
-    racc[cg][qd] = acc;
-    rl[cg][qd] = L;
-    __syncthreads();
-    if (cg != 0) return;
-    for (int g = 1; g < NG; ++g) {
-        acc += racc[g][qd];
-        L += rl[g][qd];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            if (c0 + j >= a.n_chunks) break;
+            const float mn = fmaxf(mg, ml[j].x);
+            const float e_old = __builtin_amdgcn_exp2f(mg - mn), e_new = __builtin_amdgcn_exp2f(ml[j].x - mn);
+            L = L * e_old + ml[j].y * e_new;
+            acc = acc * e_old + o[j] * e_new;
+            mg = mn;
+        }
     }
     acc *= L > 0.f ? 1.0f / L : 0.f;
     if (a.out_f32) {
@@ -489,7 +490,10 @@ void launch_t(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
     const dim3 grid(a.n_chunks, a.n_rg, z), block(kStreams * NRT * 64);
     if (a.q_f32) hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), grid, block, 0, st, a, sm);
     else hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), grid, block, 0, st, a, sm);
-    hipLaunchKernelGGL((attn_merge_kernel<D, NRT>), dim3(NRT * 32, z * a.n_rg), dim3(D * 2), 0, st, a, sm);
+    constexpr int Q4 = NRT * (D / 32) * 4 * 64;
+    const dim3 mgrid((Q4 + 255) / 256, z * a.n_rg);
+    if (a.n_chunks <= 4) hipLaunchKernelGGL((attn_merge_kernel<D, NRT, 4>), mgrid, dim3(256), 0, st, a, sm);
+    else hipLaunchKernelGGL((attn_merge_kernel<D, NRT, 16>), mgrid, dim3(256), 0, st, a, sm);
 }
 
 }  // namespace
