@@ -19,7 +19,11 @@ mirrored by the library): strict ancestors plus a separate own-slot causal
 clause; rotate-half rotary convention with base 1e6; no biases; eps 1e-6;
 untied LM head; softmax scale 1/sqrt(D); append-then-attend inside a step;
 first token of a field is a given start token at slot offset 0; lowest index
-wins argmax ties.
+wins argmax ties.  The workloads hold the KV cache in bf16 ("bf16 weights and
+KV"; Sec. 4.1: BFloat16 for most calculations): with kv_bf16=True the oracle
+rounds K and V to bf16 at the moment it stores them in its cache - a storage
+format, like the bf16 weights - and still computes everything in fp64.  The
+default (False) is the unrounded definition the CPU pins use.
 """
 from __future__ import annotations
 
@@ -201,6 +205,16 @@ def _f64(a):
     return np.asarray(a, dtype=F64)
 
 
+def to_bf16(x):
+    """Nearest bf16 value (ties to even) of every element, returned as fp64.
+    bf16 keeps the top 16 bits of the fp32 pattern: round the fp32 value there."""
+    f = np.ascontiguousarray(x, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    keep = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    out = keep.astype(np.uint32).view(np.float32).astype(F64)
+    return np.where(np.isfinite(f), out, f.astype(F64))
+
+
 class OracleDecoder:
     """fp64 decoder with a position-indexed KV cache and per-scene valid lengths.
 
@@ -210,8 +224,9 @@ class OracleDecoder:
     or of a not-yet-decoded token poisons the result instead of hiding.
     """
 
-    def __init__(self, dims, weights, prefix_len, slot_len, edges, n_scenes=1):
+    def __init__(self, dims, weights, prefix_len, slot_len, edges, n_scenes=1, kv_bf16=False):
         check_template(len(slot_len), edges)
+        self.kv_bf16 = bool(kv_bf16)
         self.d = dims
         self.w = weights
         self.prefix_len = int(prefix_len)
@@ -331,6 +346,8 @@ class OracleDecoder:
         for l in range(d.n_layers):
             lw = self.layer(l)
             q, k, v = self._qkv(lw, x, pos)
+            if self.kv_bf16:                                 # the cache's storage format
+                k, v = to_bf16(k), to_bf16(v)
             for i, (_, b, f, o) in enumerate(rows):          # append ...
                 self.K[l, b, :, pos[i]] = k[i]
                 self.V[l, b, :, pos[i]] = v[i]

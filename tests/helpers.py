@@ -27,12 +27,14 @@ def as_f32(a):
 class Pair:
     """Oracle decoder + GPU context over the same model, template and prefix."""
 
-    def __init__(self, dims, tpl, weights, n_scenes=1, max_branches=None, max_tokens=1):
+    def __init__(self, dims, tpl, weights, n_scenes=1, max_branches=None, max_tokens=1, kv_bf16=True):
         from paper_2602_02864_amd import Context
         self.dims, self.tpl, self.w, self.B = dims, tpl, weights, n_scenes
         F = tpl.n_fields
         self.Rmax = max_branches or F
-        self.dec = O.OracleDecoder(dims, weights, tpl.prefix_len, tpl.slot_len, tpl.edges, n_scenes)
+        # the library's cache is bf16: the oracle stores its K/V in that format too
+        self.dec = O.OracleDecoder(dims, weights, tpl.prefix_len, tpl.slot_len, tpl.edges, n_scenes,
+                                   kv_bf16=kv_bf16)
         self.ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, n_scenes, self.Rmax, max_tokens)
         layers = weights["layers"]
         for l in range(dims.n_layers):

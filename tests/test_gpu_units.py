@@ -227,3 +227,40 @@ def test_kv_append_skips_bad_rows_and_error_paths():
         ctx.set_valid_len([5, 0])
     assert e.value.code == fb.FDC_ERANGE
     ctx.close()
+
+
+def test_masked_attention_full_size_benchmark_configuration_sampled():
+    """Workload 3 exactly as bench.py times it (16 scenes, 32/8 heads x 128,
+    prefix 4096, 16 branches x 64-token slots, every branch active at offset 32,
+    all other slots full), oracle on sampled rows."""
+    torch = _torch()
+    from paper_2602_02864_amd import Context
+    from synth_inputs import model_dims, workload_seed
+    dims = model_dims(3)
+    tpl = template(3, rho=0.3)
+    B, F, S, P = 16, tpl.n_fields, tpl.slot_len[0], tpl.prefix_len
+    N = P + F * S
+    Hq, Hkv, D = dims.n_q_heads, dims.n_kv_heads, dims.head_dim
+    rng = workload_seed(3, "prefix", 11)
+    ctx = Context(dims, tpl.slot_len, tpl.edges, P, B, F, 1)
+    keep = {}
+    for b in range(B):                                    # one scene at a time: bounded host memory
+        Kb = draw_normal_bf16(rng, (N, Hkv, D))
+        Vb = draw_normal_bf16(rng, (N, Hkv, D))
+        ctx.kv_append(0, Kb, Vb, np.full(N, b, dtype=np.int32), np.arange(N, dtype=np.int32))
+        if b in (0, 7, 15):
+            keep[b] = (np.ascontiguousarray(Kb.transpose(1, 0, 2)), np.ascontiguousarray(Vb.transpose(1, 0, 2)))
+    ctx.set_valid_len(np.full((B, F), S, dtype=np.int32))
+    bf = np.tile(np.arange(F, dtype=np.int32), B)
+    bo = np.full(B * F, 32, dtype=np.int32)
+    q = draw_normal_bf16(rng, (B * F, Hq, D))
+    out = ctx.masked_attention(0, q, bf, bo)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().reshape(B * F, Hq, D)
+    assert np.isfinite(got).all()
+    for b, (Kb, Vb) in keep.items():
+        rows = [b * F + f for f in (0, 5, 15)]
+        ref = O.attention_only(q[rows], Kb, Vb, P, tpl.slot_len, tpl.edges, [S] * F, [0, 5, 15], [32] * 3,
+                               Hq // Hkv)
+        assert rel_err(got[rows], ref) < 2e-3
+    ctx.close()

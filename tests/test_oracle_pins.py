@@ -218,6 +218,29 @@ def test_attention_single_key_and_against_sdpa():
     assert np.allclose(got, want[0].permute(1, 0, 2).numpy(), rtol=1e-12, atol=1e-12)
 
 
+def test_bf16_storage_rounding_matches_torch_and_is_off_by_default():
+    rng = np.random.default_rng(9)
+    x = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-6, 6, 4000),
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.0e38, -1e-40]])   # incl. exact ties
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(O.to_bf16(x), want)
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert O.to_bf16(np.array([1.00390625]))[0] == 1.0 and O.to_bf16(np.array([1.01171875]))[0] == 1.015625
+    tpl = edgeless_template(2, 2, 3, TINY.vocab)
+    w, prefix = _tiny_setup(tpl, seed_cfg=7)
+    outs = {}
+    for flag in (False, True):
+        dec = O.OracleDecoder(TINY, w, 3, tpl.slot_len, tpl.edges, kv_bf16=flag)
+        assert dec.kv_bf16 is flag
+        dec.prefill_prefix(0, prefix)
+        dec.step([[0]], [[0]], tok_in=[[[1]]])
+        outs[flag] = dec.step([[0]], [[1]], tok_in=[[[2]]])["logits"][0]
+        k = dec.K[0, 0, 0, 3]
+        assert np.array_equal(k, O.to_bf16(k)) is flag      # stored K is bf16 only when asked for
+    assert O.OracleDecoder(TINY, w, 3, tpl.slot_len, tpl.edges).kv_bf16 is False
+    assert 0 < np.max(np.abs(outs[True] - outs[False])) < 2e-2 * np.max(np.abs(outs[False]))
+
+
 # ----------------------------------------------- an independent plain decoder
 def _torch_reference_logits(dims, w, x_rows, pos_ids):
     """Ordinary causal decoder over one sequence, written with torch's library
