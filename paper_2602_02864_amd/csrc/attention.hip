@@ -421,6 +421,288 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     }
 }
 
+// ---------------------------------------------------------------------------
+// Register variant.  Four independent wavefronts per workgroup; each takes every
+// fourth active tile of the chunk, handles ALL row tiles of the row group for
+// it, and fetches its tiles straight into registers (one tile ahead), so there
+// is no LDS traffic for K/V and no barrier in the loop.  The four softmax
+// states meet in LDS at the end (fixed order).
+template <int D, int NRT, bool QF32>
+__global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepMeta sm) {
+    constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, NT = 256;
+    constexpr int TILE = 32 * D;
+    __shared__ uint16_t vis[NR][kMaxFields + 2];
+    __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
+    __shared__ uint32_t tile_any[kMaxMaskedTiles];
+    __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
+    __shared__ int s_start[kMaxFields];
+    __shared__ uint16_t act_list[kMaxChunkTiles];
+    __shared__ int n_act_sh;
+    __shared__ float red_m[4][NR], red_l[4][NR];
+    __shared__ f32x4 red_o[NRT * DT * 4 * 64];
+    __shared__ bf16x8 qlo[QF32 ? NRT * DJ * 64 : 1];
+
+    const int chunk = blockIdx.x, rg = blockIdx.y, z = blockIdx.z;
+    const int b = z / a.Hkv, kvh = z % a.Hkv;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int r32 = lane & 31, hh = lane >> 5;
+    const int F = sm.F;
+    const int cb0 = chunk * a.CB, blk_end = min(a.NB, cb0 + a.CB);
+    const int mt0 = max(cb0, a.P >> 5);
+    const int nmt = max(0, blk_end - mt0);
+
+    for (int r = tid; r < NR; r += NT) {
+        const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
+        row_m[r] = ri.m;
+        row_head[r] = ri.head;
+        row_field[r] = ri.field;
+        row_off[r] = ri.off;
+    }
+    if (nmt > 0) {
+        for (int g = tid; g < F; g += NT) s_start[g] = sm.slot_start[g];
+        __syncthreads();
+        for (int idx = tid; idx < NR * F; idx += NT) {
+            const int r = idx / F, g = idx % F;
+            const int f = row_field[r];
+            int n = 0;
+            if (f >= 0) {
+                if (g == f) n = row_off[r] + 1;
+                else if ((a.anc[f] >> g) & 1ull) n = sm.valid_len[b * F + g];
+            }
+            vis[r][g] = (uint16_t)n;
+        }
+        __syncthreads();
+        for (int idx = tid; idx < nmt * NR; idx += NT) {
+            const int t = idx / NR, r = idx % NR;
+            const int key0 = (mt0 + t) * 32;
+            uint32_t bits = 0;
+            if (row_m[r] >= 0) {
+                if (key0 < a.P) {
+                    const int nb = min(a.P - key0, 32);
+                    bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
+                }
+                for (int g = 0; g < F; ++g) {
+                    const int s0 = s_start[g];
+                    if (s0 >= key0 + 32) break;
+                    const int lo = max(s0, key0), hi = min(s0 + (int)vis[r][g], key0 + 32);
+                    if (hi > lo) {
+                        const int nb = hi - lo;
+                        bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
+                    }
+                }
+            }
+            rowmask[t][r] = bits;
+        }
+        __syncthreads();
+        for (int t = wave; t < nmt; t += 4) {
+            uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
+            for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
+            if (lane == 0) tile_any[t] = v;
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int base = 0;
+        for (int c0 = 0; c0 < a.CB; c0 += 64) {               // CB <= kMaxChunkTiles
+            const int blk = cb0 + c0 + lane;
+            bool actv = blk < blk_end;
+            if (actv && blk >= mt0) actv = tile_any[blk - mt0] != 0u;
+            const unsigned long long mask = __ballot(actv);
+            if (actv) act_list[base + __popcll(mask & ((1ull << lane) - 1ull))] = (uint16_t)blk;
+            base += __popcll(mask);
+        }
+        if (lane == 0) n_act_sh = base;
+    }
+    // query operand: head (bf16) in registers, tail in LDS
+    Frag qh[NRT][DJ];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+        const int r = rt * 32 + r32;
+        const int m = row_m[r];
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) {
+            Frag lo;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) qh[rt][j].u[k] = lo.u[k] = 0;
+            if (m >= 0) {
+                const size_t qo = ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh;
+                if (QF32) {
+                    const f32x4 q0 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo);
+                    const f32x4 q1 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 4);
+                    split2(q0[0], q0[1], qh[rt][j].u[0], lo.u[0]);
+                    split2(q0[2], q0[3], qh[rt][j].u[1], lo.u[1]);
+                    split2(q1[0], q1[1], qh[rt][j].u[2], lo.u[2]);
+                    split2(q1[2], q1[3], qh[rt][j].u[3], lo.u[3]);
+                } else {
+                    qh[rt][j].v = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo);
+                }
+            }
+            if (QF32 && wave == 0) qlo[(rt * DJ + j) * 64 + lane] = lo.v;
+        }
+    }
+    __syncthreads();
+    const int n_act = n_act_sh;
+
+    f32x16 o[NRT][DT];
+    float m_run[NRT], l_run[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+        m_run[rt] = kNegBig;
+        l_run[rt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[rt][dt][i] = 0.f;
+    }
+    const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
+    auto load_tile = [&](int blk, Frag (&kf)[DJ], Frag (&vf)[DT][2]) {
+        const uint16_t* kt = a.kc + (tile_base + blk) * TILE + lane * 8;
+        const uint16_t* vt = a.vc + (tile_base + blk) * TILE + lane * 8;
+#pragma unroll
+        for (int j = 0; j < DJ; ++j)
+            kf[j].v = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(kt + j * 512));
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                vf[dt][s].v = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(vt + (dt * 2 + s) * 512));
+    };
+    auto tile = [&](auto masked_tag, int blk, Frag (&kf)[DJ], Frag (&vf)[DT][2]) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        uint32_t anyb = 0xffffu;
+        if (MASKED) {
+            anyb = lane_bits(tile_any[blk - mt0], hh);
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t wm = ((anyb >> (8 * s + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
+                                        ((anyb >> (8 * s + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) vf[dt][s].u[k] &= wm;
+                }
+        }
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+            uint32_t vbits = 0xffffu;
+            if (MASKED) vbits = lane_bits(rowmask[blk - mt0][rt * 32 + r32], hh);
+            f32x16 sc;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) sc[k] = 0.f;
+#pragma unroll
+            for (int j = 0; j < DJ; ++j) {
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qh[rt][j].v, sc, 0, 0, 0);
+                if (QF32)
+                    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qlo[(rt * DJ + j) * 64 + lane], sc, 0, 0, 0);
+            }
+            float mx = kNegBig;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                if (MASKED) sc[k] = (vbits >> k & 1u) ? sc[k] : kNegBig;
+                mx = fmaxf(mx, sc[k]);
+            }
+            mx = fmaxf(mx, other_half(mx, hh));
+            const float m_new = fmaxf(m_run[rt], mx * a.scale_log2);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+            m_run[rt] = m_new;
+            float psum = 0.f;
+            float p[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                p[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[k], a.scale_log2, -m_new));
+                if (MASKED) p[k] = (vbits >> k & 1u) ? p[k] : 0.f;
+                psum += p[k];
+            }
+            l_run[rt] = l_run[rt] * alpha + psum;
+            Frag ph[2], pl[2];
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    split2(p[8 * s + 2 * k], p[8 * s + 2 * k + 1], ph[s].u[k], pl[s].u[k]);
+            if (__any(alpha != 1.0f)) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) o[rt][dt][k] *= alpha;
+            }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    o[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, ph[s].v, o[rt][dt], 0, 0, 0);
+                    o[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s].v, pl[s].v, o[rt][dt], 0, 0, 0);
+                }
+        }
+    };
+
+    Frag kn[DJ], vn[DT][2];
+    int i = wave;
+    if (i < n_act) load_tile(act_list[i], kn, vn);
+    while (i < n_act) {
+        // keeps the query tail in LDS (re-read per tile) instead of in registers
+        if (QF32) asm volatile("" ::: "memory");
+        Frag kf[DJ], vf[DT][2];
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) kf[j] = kn[j];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            vf[dt][0] = vn[dt][0];
+            vf[dt][1] = vn[dt][1];
+        }
+        const int blk = act_list[i];
+        const int nxt = i + 4;
+        if (nxt < n_act) load_tile(act_list[nxt], kn, vn);      // in flight during this tile's math
+        if (blk >= mt0) tile(std::true_type{}, blk, kf, vf);
+        else tile(std::false_type{}, blk, kf, vf);
+        i = nxt;
+    }
+
+    // ---- merge the four wavefronts (fixed order), emit one partial ---------------
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+        l_run[rt] += other_half(l_run[rt], hh);
+        if (hh == 0) red_m[wave][rt * 32 + r32] = m_run[rt];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+        const int r = rt * 32 + r32;
+        const float mg = fmaxf(fmaxf(red_m[0][r], red_m[1][r]), fmaxf(red_m[2][r], red_m[3][r]));
+        const float e = __builtin_amdgcn_exp2f(m_run[rt] - mg);
+        if (hh == 0) red_l[wave][r] = l_run[rt] * e;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) o[rt][dt][k] *= e;
+    }
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const f32x4 v = {o[rt][dt][4 * i4], o[rt][dt][4 * i4 + 1], o[rt][dt][4 * i4 + 2],
+                                         o[rt][dt][4 * i4 + 3]};
+                        const int idx = ((rt * DT + dt) * 4 + i4) * 64 + lane;
+                        if (w == 0) red_o[idx] = v;
+                        else red_o[idx] += v;
+                    }
+        }
+        __syncthreads();
+    }
+    const size_t pidx = ((size_t)z * a.n_rg + rg) * a.n_chunks + chunk;
+    f32x4* po = reinterpret_cast<f32x4*>(a.part_o) + pidx * (NRT * DT * 4 * 64);
+    for (int q = tid; q < NRT * DT * 4 * 64; q += 256) po[q] = red_o[q];
+    if (tid < NR) {
+        float* ml = a.part_ml + (pidx * NR + tid) * 2;
+        ml[0] = fmaxf(fmaxf(red_m[0][tid], red_m[1][tid]), fmaxf(red_m[2][tid], red_m[3][tid]));
+        ml[1] = red_l[0][tid] + red_l[1][tid] + red_l[2][tid] + red_l[3][tid];
+    }
+}
+
 // Merge the chunks' partials of one (scene, kv head, row group) in chunk order.
 // One thread per accumulator quad (4 consecutive head-dim elements of one row) in
 // the partial's own order, so reads are contiguous; chunks are fetched four at a
@@ -488,8 +770,13 @@ template <int D, int NRT>
 void launch_t(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
     const int z = sm.B * a.Hkv;
     const dim3 grid(a.n_chunks, a.n_rg, z), block(kStreams * NRT * 64);
-    if (a.q_f32) hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), grid, block, 0, st, a, sm);
-    else hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), grid, block, 0, st, a, sm);
+    if (a.variant == 1) {
+        if (a.q_f32) hipLaunchKernelGGL((attn_partial_reg_kernel<D, NRT, true>), grid, dim3(256), 0, st, a, sm);
+        else hipLaunchKernelGGL((attn_partial_reg_kernel<D, NRT, false>), grid, dim3(256), 0, st, a, sm);
+    } else {
+        if (a.q_f32) hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), grid, block, 0, st, a, sm);
+        else hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), grid, block, 0, st, a, sm);
+    }
     constexpr int Q4 = NRT * (D / 32) * 4 * 64;
     const dim3 mgrid((Q4 + 255) / 256, z * a.n_rg);
     if (a.n_chunks <= 4) hipLaunchKernelGGL((attn_merge_kernel<D, NRT, 4>), mgrid, dim3(256), 0, st, a, sm);

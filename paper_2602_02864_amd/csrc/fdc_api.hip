@@ -42,7 +42,7 @@ struct fdc_ctx {
     GemmPlan p_qkv, p_o, p_gu, p_down, p_lm;
 
     // attention launch shape for the largest step
-    int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1;
+    int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1, attn_variant = 0;
 
     // workspace
     char* ws = nullptr;
@@ -119,6 +119,7 @@ void plan_attention(fdc_ctx* c) {
     if (masked_total > kMaxMaskedTiles) cb = std::min(cb, (long)kMaxMaskedTiles);
     c->attn_cb = (int)cb;
     c->attn_chunks = (int)((c->NB + cb - 1) / cb);
+    if (const char* e = std::getenv("FDC_ATTN_VARIANT")) c->attn_variant = std::atoi(e) == 1 ? 1 : 0;
 }
 
 size_t carve(fdc_ctx* c) {
@@ -224,6 +225,7 @@ void fill_attn(const fdc_ctx* c, int layer, int R, int T, AttnArgs* a) {
     a->CB = c->attn_cb;
     a->n_chunks = c->attn_chunks;
     a->nrt = c->attn_nrt;
+    a->variant = c->attn_variant;
     const int NR = a->nrt * 32;
     a->n_rg = (rows + NR - 1) / NR;
     a->scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m.head_dim));

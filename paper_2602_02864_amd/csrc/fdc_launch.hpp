@@ -89,6 +89,7 @@ struct AttnArgs {
     uint16_t* out_hi;         // ... or fragments with K = Hq*D
     uint16_t* out_lo;
     int Hq, Hkv, G, D, P, NB, CB, n_chunks, n_rg, nrt;
+    int variant;              // 0: LDS-shared tiles (direct-to-LDS ring), 1: tiles in registers
     float scale_log2;         // log2(e) / sqrt(D)
 };
 void launch_attention(const AttnArgs& a, const StepMeta& sm, hipStream_t st);
