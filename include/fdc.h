@@ -261,6 +261,22 @@ int32_t     fdc_profile_read(fdc_ctx* ctx, float* ms_sum /* host [FDC_PROF_KINDS
                              int32_t* launches /* host [FDC_PROF_KINDS] */);
 const char* fdc_profile_kind_name(int32_t kind);   /* NULL outside 0..FDC_PROF_KINDS-1 */
 
+/* What an event pair adds to the launch it brackets: `rounds` times a kernel is
+ * timed once and twice between two events on `stream`; the difference is one
+ * launch (*null_us, may be NULL), the remainder of the single-launch time is the
+ * cost of the pair (*overhead_us), which a benchmark subtracts from its
+ * per-kernel event times.  The kernel is a copy of one half of `scratch` (device,
+ * 256-byte aligned, caller-owned, contents destroyed) onto the other, or an
+ * empty kernel when scratch is NULL.  Synchronises the stream.  Host pointers
+ * for the results. */
+int32_t fdc_profile_calibrate(int32_t rounds, void* scratch, size_t scratch_bytes, float* overhead_us,
+                              float* null_us, void* stream);
+
+/* Plain streaming copy of `bytes` (multiple of 16) between two device buffers
+ * (16-byte aligned, not overlapping): the sustained-bandwidth reference of the
+ * device, and the known-size kernel that hardware traffic counters are scaled by. */
+int32_t fdc_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

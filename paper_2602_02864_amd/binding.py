@@ -30,6 +30,7 @@ EXPORTS = [
     "fdc_get_valid_len", "fdc_kv_append", "fdc_parallel_decode_step", "fdc_masked_attention",
     "fdc_argmax", "fdc_linear_scratch_bytes", "fdc_linear",
     "fdc_profile_enable", "fdc_profile_read", "fdc_profile_kind_name",
+    "fdc_profile_calibrate", "fdc_stream_copy",
     "fdc_sched_create", "fdc_sched_next", "fdc_sched_destroy",
 ]
 FDC_PROF_KINDS = 9
@@ -121,6 +122,10 @@ def lib() -> C.CDLL:
     L.fdc_profile_read.argtypes = [vp, C.POINTER(C.c_float), pi32]
     L.fdc_profile_kind_name.restype = C.c_char_p
     L.fdc_profile_kind_name.argtypes = [i32]
+    L.fdc_profile_calibrate.restype = i32
+    L.fdc_profile_calibrate.argtypes = [i32, vp, sz, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
+    L.fdc_stream_copy.restype = i32
+    L.fdc_stream_copy.argtypes = [vp, vp, sz, vp]
     L.fdc_sched_create.restype = i32
     L.fdc_sched_create.argtypes = [i32, i32, pi32, pi32, pi32, C.POINTER(vp)]
     L.fdc_sched_next.restype = i32
@@ -243,6 +248,25 @@ def fdc_linear(x, w_packed, n_out: int):
     _check(lib().fdc_linear(x.data_ptr(), w_packed.data_ptr(), y.data_ptr(), M, n_out, k_in,
                             scratch.data_ptr(), _stream()))
     return y
+
+
+def fdc_profile_calibrate(rounds: int = 200, scratch=None):
+    """(cost of an event pair around one launch, duration of that launch), microseconds.
+    The launch copies half of the device tensor `scratch` onto its other half; without
+    scratch it is an empty kernel."""
+    ov, nul = C.c_float(0), C.c_float(0)
+    ptr = scratch.data_ptr() if scratch is not None else None
+    nb = scratch.numel() * scratch.element_size() if scratch is not None else 0
+    _check(lib().fdc_profile_calibrate(rounds, ptr, nb, C.byref(ov), C.byref(nul), _stream()))
+    return float(ov.value), float(nul.value)
+
+
+def fdc_stream_copy(dst, src) -> None:
+    """dst <- src for two device tensors of equal byte size (multiple of 16)."""
+    nb = src.numel() * src.element_size()
+    if nb != dst.numel() * dst.element_size() or not (src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("copy needs contiguous tensors of equal byte size")
+    _check(lib().fdc_stream_copy(dst.data_ptr(), src.data_ptr(), nb, _stream()))
 
 
 class Context:

@@ -105,11 +105,15 @@ void plan_attention(fdc_ctx* c) {
     c->attn_nrt = rows > 32 ? 2 : 1;
     const int NR = c->attn_nrt * 32;
     c->attn_rg_max = (rows + NR - 1) / NR;
-    // One workgroup per compute unit is resident at head_dim 128 (the K/V ring
-    // takes most of LDS), two at 64: aim at that many workgroups in total, at
-    // least two tiles per stream, within the kernel's per-chunk limits.
+    // A layer's K/V of tens of megabytes and more is a bandwidth problem: one
+    // workgroup per compute unit (two at head_dim 64), tiles fetched straight
+    // into registers.  Below that the call is a chain of latencies and fewer,
+    // longer chunks (a shorter merge) with LDS-shared tiles measure faster.
     const long zr = (long)c->B * c->m.n_kv_heads * c->attn_rg_max;
-    long want_wgs = 256L * (c->m.head_dim == 128 ? 1 : 2);
+    const double layer_kv_bytes = 4.0 * c->B * c->m.n_kv_heads * (double)c->Npad * c->m.head_dim;
+    const bool large = layer_kv_bytes >= 64e6;
+    c->attn_variant = large ? 1 : 0;
+    long want_wgs = (large ? 256L : 64L) * (c->m.head_dim == 128 ? 1 : 2);
     if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
     long chunks = std::max(1L, (want_wgs + zr / 2) / zr);
     long cb = (c->NB + chunks - 1) / chunks;
@@ -697,6 +701,55 @@ int32_t fdc_profile_read(fdc_ctx* c, float* ms_sum, int32_t* launches) {
         c->prof_pool.push_back(r);
     }
     c->prof_recs.clear();
+    return FDC_OK;
+}
+
+int32_t fdc_profile_calibrate(int32_t rounds, void* scratch, size_t scratch_bytes, float* overhead_us,
+                              float* null_us, void* stream) {
+    if (!overhead_us || rounds < 1 || rounds > 10000) return fail(FDC_EINVAL, "bad calibration arguments");
+    if (scratch && (!aligned(scratch, 256) || scratch_bytes < 512)) return fail(FDC_EINVAL, "bad calibration scratch");
+    const size_t half = scratch ? scratch_bytes / 2 / 256 * 256 : 0;
+    auto launch_one = [&](hipStream_t s) {
+        if (half) launch_stream_copy(scratch, (char*)scratch + half, half, s);
+        else launch_null(s);
+    };
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e[2] = {nullptr, nullptr};
+    FDC_HIP(hipEventCreate(&e[0]));
+    if (hipEventCreate(&e[1]) != hipSuccess) {
+        (void)hipEventDestroy(e[0]);
+        return fail(FDC_EHIP, "event creation failed");
+    }
+    // one launch between two events against two launches between two events:
+    // the difference is one launch, the rest of the first is the pair's cost
+    double sum1 = 0.0, sum2 = 0.0;
+    hipError_t err = hipSuccess;
+    for (int n = 1; n <= 2 && err == hipSuccess; ++n)
+        for (int r = 0; r < rounds + 3 && err == hipSuccess; ++r) {
+            err = hipEventRecord(e[0], st);
+            for (int i = 0; i < n; ++i) launch_one(st);
+            if (err == hipSuccess) err = hipEventRecord(e[1], st);
+            if (err == hipSuccess) err = hipEventSynchronize(e[1]);
+            float ms = 0.f;
+            if (err == hipSuccess) err = hipEventElapsedTime(&ms, e[0], e[1]);
+            if (r >= 3) (n == 1 ? sum1 : sum2) += ms;
+        }
+    (void)hipEventDestroy(e[0]);
+    (void)hipEventDestroy(e[1]);
+    if (err != hipSuccess) return fail(FDC_EHIP, "calibration: %s", hipGetErrorString(err));
+    const double t1 = 1e3 * sum1 / rounds, t2 = 1e3 * sum2 / rounds;
+    const double one = std::max(0.0, t2 - t1);
+    *overhead_us = (float)std::max(0.0, t1 - one);
+    if (null_us) *null_us = (float)one;
+    return FDC_OK;
+}
+
+int32_t fdc_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src) return fail(FDC_EINVAL, "null pointer argument");
+    if (!aligned(dst) || !aligned(src) || bytes % 16) return fail(FDC_EINVAL, "copy needs 16-byte alignment and size");
+    if (bytes == 0) return FDC_OK;
+    launch_stream_copy(src, dst, bytes, (hipStream_t)stream);
+    FDC_HIP(hipGetLastError());
     return FDC_OK;
 }
 

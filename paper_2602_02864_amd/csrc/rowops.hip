@@ -235,7 +235,29 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     }
 }
 
+// measurement helpers: an empty kernel (what an event pair costs around a
+// launch) and a streaming copy (what the device's HBM sustains, and the
+// reference the traffic counters are scaled by)
+__global__ void null_kernel() {}
+
+typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_copy_kernel(const copy_u32x4* __restrict__ src,
+                                                          copy_u32x4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
+}
+
 }  // namespace
+
+void launch_null(hipStream_t st) { null_kernel<<<1, 64, 0, st>>>(); }
+
+void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 256 * 8 - 1) / (256 * 8);
+    const unsigned grid = (unsigned)std::min<size_t>(std::max<size_t>(want, 1), 256 * 16);
+    stream_copy_kernel<<<grid, 256, 0, st>>>((const copy_u32x4*)src, (copy_u32x4*)dst, n16);
+}
 
 void launch_resid_norm(const NormArgs& a, const StepMeta& sm, hipStream_t st) {
     hipLaunchKernelGGL(resid_norm_kernel, dim3(a.M), dim3(256), 0, st, a, sm);

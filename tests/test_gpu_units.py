@@ -264,3 +264,20 @@ def test_masked_attention_full_size_benchmark_configuration_sampled():
                                Hq // Hkv)
         assert rel_err(got[rows], ref) < 2e-3
     ctx.close()
+
+
+def test_stream_copy_and_event_calibration():
+    """Measurement helpers: the copy is exact (ragged size), misuse is refused, and
+    the event-pair overhead is a small non-negative number of microseconds."""
+    import torch
+    from paper_2602_02864_amd import FdcError, fdc_profile_calibrate, fdc_stream_copy
+    n = (1 << 22) + 16 * 37
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    fdc_stream_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    with pytest.raises(FdcError):
+        fdc_stream_copy(dst[:24], src[:24])          # not a multiple of 16 bytes
+    ov, nul = fdc_profile_calibrate(50)
+    assert 0.0 <= ov < 100.0 and 0.0 <= nul < 100.0
