@@ -11,7 +11,8 @@ run and one `--pmc WRITE_SIZE` run of the same command, scales each counter by
 what it shows for the library's streaming copy of known size (which reads and
 writes exactly --copy-bytes), and prints HBM bytes per launch for every kernel;
 with --json it records the kernels named by --kernel (label=substring of the
-kernel name) for bench.py's `roofline.traffic`.
+kernel name; several substrings joined by | are summed, for an operation made
+of several kernels) for bench.py's `roofline.traffic`.
 """
 from __future__ import annotations
 
@@ -94,7 +95,8 @@ def traffic(fetch_dir, write_dir, copy_bytes, workload, kernels, json_path):
             rec = {}
         for spec in kernels:
             label, _, pat = spec.partition("=")
-            hits = [k for k in out if pat.replace(" ", "") in k.replace(" ", "")]
+            pats = [q.replace(" ", "") for q in pat.split("|")]
+            hits = [k for k in out if any(q in k.replace(" ", "") for q in pats)]
             if not hits:
                 raise SystemExit(f"no kernel matches {pat!r}")
             r = sum(out[k][0] for k in hits)
