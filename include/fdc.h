@@ -241,8 +241,9 @@ int32_t fdc_argmax(const float* logits, int32_t M, int32_t V, int64_t ld,
                    int32_t* idx_out, float* top2_gap_out, void* stream);
 
 /* One dense projection y[M][n_out] = x[M][k_in] * W^T with W packed, x and y
- * device fp32 row-major, M <= 16; `scratch` device, fdc_linear_scratch_bytes().
- * Exposes the projection kernels of the step for tests and measurements. */
+ * device fp32 row-major, M <= 1024; `scratch` device, fdc_linear_scratch_bytes().
+ * Exposes the projection kernels of the step for tests and measurements: up to
+ * 16 rows the weight-streaming kernel, above it the tiled matrix-core kernel. */
 size_t  fdc_linear_scratch_bytes(int32_t M, int64_t n_out, int64_t k_in);
 int32_t fdc_linear(const float* x, const void* w_packed, float* y,
                    int32_t M, int64_t n_out, int64_t k_in, void* scratch, void* stream);

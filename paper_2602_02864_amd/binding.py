@@ -243,7 +243,8 @@ def fdc_linear(x, w_packed, n_out: int):
     nbytes = int(lib().fdc_linear_scratch_bytes(M, n_out, k_in))
     if nbytes == 0:
         raise FdcError(FDC_ECAP, "shape not supported by fdc_linear")
-    scratch = torch.zeros(nbytes, dtype=torch.uint8, device=x.device)
+    # scratch arrives as NaN patterns: rows beyond M must never leak into y
+    scratch = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=x.device)
     y = torch.empty(M, n_out, dtype=torch.float32, device=x.device)
     _check(lib().fdc_linear(x.data_ptr(), w_packed.data_ptr(), y.data_ptr(), M, n_out, k_in,
                             scratch.data_ptr(), _stream()))

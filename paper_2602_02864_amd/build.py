@@ -17,13 +17,17 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfdc.so")
-SOURCES = ["fdc_host.cpp", "fdc_api.hip", "gemm_skinny.hip", "rowops.hip", "attention.hip"]
+SOURCES = ["fdc_host.cpp", "fdc_api.hip", "gemm_skinny.hip", "gemm_tiled.hip", "rowops.hip", "attention.hip"]
+
+# matrix-instruction accumulators in ordinary VGPRs: the softmax rescales them with
+# vector ALU ops, which cannot touch accumulation registers.  The tiled GEMM is the
+# opposite case (accumulators only ever feed matrix instructions until the
+# epilogue, and there are more of them than VGPRs to spare): it keeps the default.
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+NO_VGPR_FORM = {"gemm_tiled.hip"}
 
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             # matrix-instruction accumulators in ordinary VGPRs: the softmax rescales
-             # them with vector ALU ops, which cannot touch accumulation registers
-             "-mllvm", "-amdgpu-mfma-vgpr-form=1",
              "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
@@ -51,7 +55,8 @@ def build(verbose: bool = False, jobs: int = 4) -> str:
 
     def one(src):
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc] + HIP_FLAGS + (["-x", "hip"] if src.endswith(".hip") else []) + \
+        cmd = [hipcc] + HIP_FLAGS + ([] if src in NO_VGPR_FORM else VGPR_FORM) + \
+              (["-x", "hip"] if src.endswith(".hip") else []) + \
               ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)

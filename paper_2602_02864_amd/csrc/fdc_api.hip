@@ -40,6 +40,7 @@ struct fdc_ctx {
     size_t kv_layer_elems = 0;
 
     GemmPlan p_qkv, p_o, p_gu, p_down, p_lm;
+    int Mp = kMaxRowsDense;              // rows the workspace is laid out for (multiple of 16)
 
     // attention launch shape for the largest step
     int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1, attn_variant = 0;
@@ -134,7 +135,7 @@ size_t carve(fdc_ctx* c) {
         o = align_up(o + bytes);
         return at;
     };
-    const int Mp = kMaxRowsDense;
+    const int Mp = c->Mp = std::max(kMaxRowsDense, (c->Mmax + 15) / 16 * 16);
     const size_t HqD = (size_t)m.n_q_heads * m.head_dim;
     const size_t Nqkv = (size_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
     c->off.anc = take(sizeof(uint64_t) * c->F);
@@ -151,11 +152,21 @@ size_t carve(fdc_ctx* c) {
     c->off.o_lo = take(2 * (size_t)Mp * HqD);
     c->off.h_hi = take(2 * (size_t)Mp * m.d_mlp);
     c->off.h_lo = take(2 * (size_t)Mp * m.d_mlp);
-    c->off.q = take(sizeof(float) * (size_t)kMaxRowsDense * HqD);
+    c->off.q = take(sizeof(float) * (size_t)Mp * HqD);
+    // split-K partials: the streaming kernels' splits for up to 16 rows, the
+    // tiled kernels' for every larger step shape this context admits
     size_t part = 0;
-    part = std::max(part, (size_t)c->p_qkv.S * Mp * Nqkv);
-    part = std::max(part, (size_t)c->p_o.S * Mp * m.d_model);
-    part = std::max(part, (size_t)c->p_down.S * Mp * m.d_model);
+    part = std::max(part, (size_t)c->p_qkv.S * kMaxRowsDense * Nqkv);
+    part = std::max(part, (size_t)c->p_o.S * kMaxRowsDense * m.d_model);
+    part = std::max(part, (size_t)c->p_down.S * kMaxRowsDense * m.d_model);
+    for (int R = 1; R <= c->Rmax; ++R)
+        for (int T = 1; T <= c->Tmax; ++T) {
+            const int M = c->B * R * T;
+            if (M <= kMaxRowsDense) continue;
+            part = std::max(part, (size_t)plan_tiled(M, Nqkv, m.d_model, false).S * M * Nqkv);
+            part = std::max(part, (size_t)plan_tiled(M, m.d_model, HqD, false).S * M * m.d_model);
+            part = std::max(part, (size_t)plan_tiled(M, m.d_model, m.d_mlp, false).S * M * m.d_model);
+        }
     c->off.part = take(sizeof(float) * part);
     c->off.logits = take(sizeof(float) * Mp * m.vocab);
     const size_t zr = (size_t)c->B * m.n_kv_heads * c->attn_rg_max;
@@ -272,6 +283,43 @@ GemmPlan plan_gemm(int64_t n_out, int64_t k_in, bool swiglu) {
     return p;
 }
 
+TiledPlan plan_tiled(int M, int64_t n_out, int64_t k_in, bool swiglu, int max_splits) {
+    TiledPlan best;
+    double best_cost = 0.0;
+    const int KT = (int)(k_in / 32), n_tiles = (int)((n_out + 15) / 16), m_tiles = (M + 15) / 16;
+    const int m_blocks = (m_tiles + 7) / 8;
+    static const int widths[] = {4, 8, 10};
+    for (int ntw : widths)
+        for (int S = 1; S <= (swiglu ? 1 : max_splits); ++S) {
+            const int kts = (KT + S - 1) / S;
+            if (S > 1 && kts < 8) break;
+            const int Seff = (KT + kts - 1) / kts;
+            const int n_groups = (n_tiles + 2 * ntw - 1) / (2 * ntw);
+            const long tasks = (long)n_groups * m_blocks * Seff;
+            const long rounds = (tasks + 255) / 256;
+            // clocks of one workgroup: per k tile the matrix pipe (8 * ntw instructions
+            // of 16 clocks per wavefront) or the LDS reads (four wavefronts, 8 + ntw
+            // fragments of 1 KiB each at 128 B per clock), plus a fixed ramp; the
+            // partials of a split cost their write and their read by the consumer
+            const double per_kt = std::max(128.0 * ntw, 32.0 * (8 + ntw));
+            const double partials = Seff > 1 ? 8.0 * Seff * M * (double)n_out / 4.0e12 * 2.4e9 : 0.0;
+            const double cost = rounds * (kts * per_kt + 4000.0) + partials;
+            if (best.grid == 0 || cost < best_cost) {
+                best_cost = cost;
+                best.KT = KT;
+                best.n_tiles = n_tiles;
+                best.m_tiles = m_tiles;
+                best.S = Seff;
+                best.kt_split = kts;
+                best.ntw = ntw;
+                best.n_groups = n_groups;
+                best.m_blocks = m_blocks;
+                best.grid = (int)((tasks + 7) / 8 * 8);
+            }
+        }
+    return best;
+}
+
 }  // namespace fdc
 
 extern "C" {
@@ -311,6 +359,8 @@ int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t*
         return fail(FDC_ECAP, "d_model and d_mlp must be multiples of 32, vocab of 4");
     if (n_fields > kMaxFields) return fail(FDC_ECAP, "n_fields %d above %d", n_fields, kMaxFields);
     if (n_scenes < 1 || max_branches < 1 || max_tokens < 1) return fail(FDC_EINVAL, "bad batch shape");
+    if ((int64_t)n_scenes * max_branches * max_tokens > kMaxRowsStep)
+        return fail(FDC_ECAP, "%lld rows per step above %d", (long long)n_scenes * max_branches * max_tokens, kMaxRowsStep);
     if (m.d_model > 8 * 20 * 32) return fail(FDC_ECAP, "d_model above %d", 8 * 20 * 32);
 
     fdc_ctx* c = new (std::nothrow) fdc_ctx;
@@ -530,7 +580,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     if (rc != FDC_OK) return rc;
     const fdc_model_desc& m = c->m;
     const int M = c->B * R * T;
-    if (M > kMaxRowsDense) return fail(FDC_ECAP, "%d rows in one step; the projections take at most %d", M, kMaxRowsDense);
+    if (M > c->Mp) return fail(FDC_ECAP, "%d rows in one step; this context was created for %d", M, c->Mp);
     if ((emb_in && !aligned(emb_in)) || (logits_out && !aligned(logits_out)) || (hidden_out && !aligned(hidden_out)))
         return fail(FDC_EINVAL, "pointers must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
@@ -560,6 +610,20 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     float* logits = logits_out ? logits_out : c->at<float>(c->off.logits);
     const size_t hstride = (size_t)M * d;
 
+    // up to 16 rows the projections stream their weights once (bandwidth-bound);
+    // above, they are tiled matrix products; either way `S` partials come back
+    const bool tiled = M > kMaxRowsDense;
+    auto project = [&](const GemmPlan& skinny, int64_t n_out, int64_t k_in, int epi, const GemmArgs& ga,
+                       bool one_split) -> int {
+        if (!tiled) {
+            launch_gemm(skinny, epi, ga, st);
+            return skinny.S;
+        }
+        const TiledPlan tp = plan_tiled(M, n_out, k_in, epi == EPI_SWIGLU, one_split ? 1 : 16);
+        launch_gemm_tiled(tp, epi, ga, st);
+        return tp.S;
+    };
+
     NormArgs na{};
     na.x = x;
     na.eps = m.norm_eps;
@@ -569,6 +633,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     na.d = d;
     na.vocab = m.vocab;
 
+    int s_down = c->p_down.S;
     for (int l = 0; l < m.n_layers; ++l) {
         const fdc_layer_weights& w = c->lw[l];
         // residual (embedding, or + MLP output of the previous layer) and attention norm
@@ -579,7 +644,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
             n1.emb_rows = (const uint16_t*)emb_in;
         } else {
             n1.part = part;
-            n1.S = c->p_down.S;
+            n1.S = s_down;
         }
         n1.gain = w.g1;
         n1.hidden_x = hidden_out ? hidden_out + (size_t)l * hstride : nullptr;
@@ -593,11 +658,12 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         g.M = M;
         g.N = Nqkv;
         g.n_valid = Nqkv;
-        { ProfScope ps_(c, PK_QKV, st); launch_gemm(c->p_qkv, EPI_PARTIAL, g, st); }
+        int s_qkv;
+        { ProfScope ps_(c, PK_QKV, st); s_qkv = project(c->p_qkv, Nqkv, d, EPI_PARTIAL, g, false); }
 
         RopeArgs ra{};
         ra.part = part;
-        ra.S = c->p_qkv.S;
+        ra.S = s_qkv;
         ra.q = q;
         ra.kc = c->kc + (size_t)l * c->kv_layer_elems;
         ra.vc = c->vc + (size_t)l * c->kv_layer_elems;
@@ -621,11 +687,12 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         g.act_lo = o_lo;
         g.N = d;
         g.n_valid = d;
-        { ProfScope ps_(c, PK_O, st); launch_gemm(c->p_o, EPI_PARTIAL, g, st); }
+        int s_o;
+        { ProfScope ps_(c, PK_O, st); s_o = project(c->p_o, d, HqD, EPI_PARTIAL, g, false); }
 
         NormArgs n2 = na;
         n2.part = part;
-        n2.S = c->p_o.S;
+        n2.S = s_o;
         n2.gain = w.g2;
         { ProfScope ps_(c, PK_NORM, st); launch_resid_norm(n2, sm, st); }
 
@@ -637,18 +704,18 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         gu.out_lo = h_lo;
         gu.out_KT = m.d_mlp / 32;
         gu.M = M;
-        { ProfScope ps_(c, PK_GATEUP, st); launch_gemm(c->p_gu, EPI_SWIGLU, gu, st); }
+        { ProfScope ps_(c, PK_GATEUP, st); project(c->p_gu, 2 * (int64_t)m.d_mlp, d, EPI_SWIGLU, gu, true); }
 
         g.w = (const uint16_t*)w.wd;
         g.act_hi = h_hi;
         g.act_lo = h_lo;
         g.N = d;
         g.n_valid = d;
-        { ProfScope ps_(c, PK_DOWN, st); launch_gemm(c->p_down, EPI_PARTIAL, g, st); }
+        { ProfScope ps_(c, PK_DOWN, st); s_down = project(c->p_down, d, m.d_mlp, EPI_PARTIAL, g, false); }
     }
     NormArgs nf = na;
     nf.part = part;
-    nf.S = c->p_down.S;
+    nf.S = s_down;
     nf.gain = c->gf;
     nf.hidden_x = hidden_out ? hidden_out + (size_t)m.n_layers * hstride : nullptr;
     nf.hidden_n = hidden_out ? hidden_out + (size_t)(m.n_layers + 1) * hstride : nullptr;
@@ -662,7 +729,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     gl.M = M;
     gl.N = m.vocab;
     gl.n_valid = m.vocab;
-    { ProfScope ps_(c, PK_LMHEAD, st); launch_gemm(c->p_lm, EPI_PARTIAL, gl, st); }
+    { ProfScope ps_(c, PK_LMHEAD, st); project(c->p_lm, m.vocab, d, EPI_PARTIAL, gl, true); }
     { ProfScope ps_(c, PK_ARGMAX, st); launch_argmax(logits, M, m.vocab, m.vocab, tok_out, gap_out, sm.branch_field, T, st); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -763,35 +830,47 @@ int32_t fdc_argmax(const float* logits, int32_t M, int32_t V, int64_t ld, int32_
 }
 
 size_t fdc_linear_scratch_bytes(int32_t M, int64_t n_out, int64_t k_in) {
-    if (M < 1 || M > kMaxRowsDense || n_out < 16 || k_in < 32) return 0;
-    const GemmPlan p = plan_gemm(n_out, k_in, false);
-    return align_up(2 * (size_t)kMaxRowsDense * k_in) * 2 + align_up(sizeof(float) * p.S * M * n_out);
+    if (M < 1 || M > kMaxRowsStep || n_out < 16 || k_in < 32) return 0;
+    const int Mp = (M + 15) / 16 * 16;
+    const int S = M <= kMaxRowsDense ? plan_gemm(n_out, k_in, false).S : plan_tiled(M, n_out, k_in, false).S;
+    return align_up(2 * (size_t)Mp * k_in) * 2 + align_up(sizeof(float) * S * M * n_out);
 }
 
 int32_t fdc_linear(const float* x, const void* w, float* y, int32_t M, int64_t n_out, int64_t k_in,
                    void* scratch, void* stream) {
     if (!x || !w || !y || !scratch) return fail(FDC_EINVAL, "null pointer argument");
-    if (M < 1 || M > kMaxRowsDense) return fail(FDC_ECAP, "M = %d outside 1..%d", M, kMaxRowsDense);
+    if (M < 1 || M > kMaxRowsStep) return fail(FDC_ECAP, "M = %d outside 1..%d", M, kMaxRowsStep);
     if (n_out <= 0 || k_in <= 0 || n_out % 4 || k_in % 32) return fail(FDC_EINVAL, "n_out must be a multiple of 4, k_in of 32");
     if (!aligned(w) || !aligned(y) || !aligned(scratch, 256)) return fail(FDC_EINVAL, "misaligned pointer");
-    const GemmPlan p = plan_gemm(n_out, k_in, false);
-    if (p.ktw == 0) return fail(FDC_ECAP, "k_in = %lld does not fit the streaming kernel", (long long)k_in);
     hipStream_t st = (hipStream_t)stream;
     char* s = (char*)scratch;
-    const size_t fb = align_up(2 * (size_t)kMaxRowsDense * k_in);
+    const int Mp = (M + 15) / 16 * 16;
+    const size_t fb = align_up(2 * (size_t)Mp * k_in);
     uint16_t *hi = (uint16_t*)s, *lo = (uint16_t*)(s + fb);
     float* part = (float*)(s + 2 * fb);
-    launch_to_frag(x, hi, lo, M, (int)k_in, st);
     GemmArgs g{};
     g.w = (const uint16_t*)w;
     g.act_hi = hi;
     g.act_lo = lo;
-    g.out = p.S == 1 ? y : part;
     g.M = M;
     g.N = (int)n_out;
     g.n_valid = (int)n_out;
-    launch_gemm(p, EPI_PARTIAL, g, st);
-    if (p.S > 1) launch_sum_partials(part, y, p.S, M, n_out, st);
+    int S;
+    if (M <= kMaxRowsDense) {
+        const GemmPlan p = plan_gemm(n_out, k_in, false);
+        if (p.ktw == 0) return fail(FDC_ECAP, "k_in = %lld does not fit the streaming kernel", (long long)k_in);
+        launch_to_frag(x, hi, lo, M, (int)k_in, st);
+        S = p.S;
+        g.out = S == 1 ? y : part;
+        launch_gemm(p, EPI_PARTIAL, g, st);
+    } else {
+        const TiledPlan p = plan_tiled(M, n_out, k_in, false);
+        launch_to_frag(x, hi, lo, M, (int)k_in, st);
+        S = p.S;
+        g.out = S == 1 ? y : part;
+        launch_gemm_tiled(p, EPI_PARTIAL, g, st);
+    }
+    if (S > 1) launch_sum_partials(part, y, S, M, n_out, st);
     FDC_HIP(hipGetLastError());
     return FDC_OK;
 }

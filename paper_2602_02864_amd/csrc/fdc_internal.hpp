@@ -15,7 +15,8 @@ int32_t build_plan(int32_t F, const int32_t* slot_len, int32_t E, const int32_t*
                    int32_t* level, int32_t* total_len);
 
 constexpr int kMaxFields = 64;      // one 64-bit ancestor word per field in the kernels
-constexpr int kMaxRowsDense = 16;   // rows per step the streaming projections take
+constexpr int kMaxRowsDense = 16;   // rows per step the streaming projections take; more go to the tiled ones
+constexpr int kMaxRowsStep = 1024;  // rows per step overall
 constexpr int kStageSlots = 8;      // pinned staging ring for per-step metadata
 constexpr int kMaxChunkTiles = 128; // 32-key tiles one attention workgroup walks at most
 constexpr int kMaxMaskedTiles = 32; // ... of which this many may reach into the slots
@@ -36,5 +37,21 @@ struct GemmPlan {
 };
 
 GemmPlan plan_gemm(int64_t n_out, int64_t k_in, bool swiglu);
+
+// The same projection for more than 16 rows: workgroups of 2 x 2 wavefronts own
+// 128 rows x (2 * ntw) 16-feature tiles, S splits of K.
+struct TiledPlan {
+    int KT = 0;        // 32-wide k tiles
+    int n_tiles = 0;   // 16-feature tiles (padded weight rows included)
+    int m_tiles = 0;   // 16-row tiles
+    int S = 1;
+    int kt_split = 0;
+    int ntw = 8;       // feature tiles per wavefront
+    int n_groups = 0;  // workgroup columns
+    int m_blocks = 0;  // workgroup rows
+    int grid = 0;
+};
+
+TiledPlan plan_tiled(int M, int64_t n_out, int64_t k_in, bool swiglu, int max_splits = 16);
 
 }  // namespace fdc

@@ -18,12 +18,13 @@ struct GemmArgs {
     float* out;               // EPI_PARTIAL: [S][M][N] fp32
     uint16_t* out_hi;         // EPI_SWIGLU: fragments of silu(g)*u for the next projection
     uint16_t* out_lo;
-    int M;                    // valid rows (<= 16)
+    int M;                    // valid rows
     int N;                    // row stride of `out`
     int n_valid;              // output features actually stored (multiple of 4)
     int out_KT;               // EPI_SWIGLU: k tiles of the consumer (= d_mlp / 32)
 };
 void launch_gemm(const GemmPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
+void launch_gemm_tiled(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
 void launch_pack_weight(const uint16_t* src, uint16_t* dst, int64_t n_out, int64_t k_in, int mode,
                         hipStream_t st);
 // x fp32 [M][K] -> hi/lo fragments (no normalisation); y = sum of S partials

@@ -37,17 +37,11 @@ def test_workload0_whole_schedule():
     pair.close()
 
 
-@pytest.mark.parametrize("seed,B,T,D", [(0, 2, 1, 64), (1, 1, 2, 128), (2, 3, 1, 128), (3, 2, 3, 64)])
-def test_random_small_models_ragged_templates(seed, B, T, D):
-    """Ragged slots and prefix, random gains, several scenes in different
-    states, inactive branch entries, multi-token steps."""
-    dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=D, d_mlp=160,
-                     vocab=500 + 4 * seed)
-    tpl = random_dag_template(900 + seed, n_fields=5, prefix_len=19 + seed, max_slot=9,
+def _random_model_steps(seed, B, T, R, dims, n_fields=5, max_slot=9, n_steps=6):
+    tpl = random_dag_template(900 + seed, n_fields=n_fields, prefix_len=19 + seed, max_slot=max_slot,
                               edge_prob=0.4, vocab=dims.vocab)
     tpl.slot_len = [max(s, T) for s in tpl.slot_len]
     w = draw_weights(10 + seed, dims, random_gains=True, std=0.05)
-    R = max(1, 16 // (B * T))
     R = min(R, tpl.n_fields)
     pair = Pair(dims, tpl, w, n_scenes=B, max_branches=R, max_tokens=T)
     for b in range(B):
@@ -55,7 +49,8 @@ def test_random_small_models_ragged_templates(seed, B, T, D):
     rng = np.random.default_rng(seed)
     F = tpl.n_fields
     done = np.zeros((B, F), dtype=int)
-    for step in range(6):
+    ran = 0
+    for step in range(n_steps):
         bf = np.full((B, R), -1, dtype=np.int32)
         bo = np.zeros((B, R), dtype=np.int32)
         for b in range(B):
@@ -69,11 +64,35 @@ def test_random_small_models_ragged_templates(seed, B, T, D):
             continue
         tok = rng.integers(0, dims.vocab, size=(B, R, T)).astype(np.int32)
         pair.step_both(bf, bo, tok, T=T, tag=f"seed{seed} step{step}")
+        ran += 1
         for b in range(B):
             for i in range(R):
                 if bf[b, i] >= 0:
                     done[b, bf[b, i]] += T
     pair.close()
+    return ran
+
+
+@pytest.mark.parametrize("seed,B,T,D", [(0, 2, 1, 64), (1, 1, 2, 128), (2, 3, 1, 128), (3, 2, 3, 64)])
+def test_random_small_models_ragged_templates(seed, B, T, D):
+    """Ragged slots and prefix, random gains, several scenes in different
+    states, inactive branch entries, multi-token steps."""
+    dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=D, d_mlp=160,
+                     vocab=500 + 4 * seed)
+    assert _random_model_steps(seed, B, T, max(1, 16 // (B * T)), dims) >= 3
+
+
+@pytest.mark.parametrize("seed,B,T,R,Hq,Hkv,D,F", [(4, 4, 2, 5, 4, 2, 64, 5),      # 40 rows
+                                                   (5, 3, 4, 6, 14, 2, 64, 8),     # 72 rows, 168 per kv head
+                                                   (6, 8, 4, 5, 8, 2, 128, 6),     # 160 rows: two row blocks
+                                                   (7, 2, 3, 3, 4, 4, 128, 4)])    # 18 rows: just above 16
+def test_many_rows_per_step_use_the_tiled_projections(seed, B, T, R, Hq, Hkv, D, F):
+    """More than 16 rows in a step (several scenes, several tokens per branch:
+    the multi-token masked prefill inside a slot): the projections switch to the
+    tiled matrix-core kernels, attention to several row groups per KV head."""
+    dims = ModelDims(n_layers=2, d_model=Hq * 32, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, d_mlp=352,
+                     vocab=600 + 4 * seed)
+    assert _random_model_steps(seed, B, T, R, dims, n_fields=F, max_slot=12, n_steps=5) >= 2
 
 
 def test_chain_dag_on_gpu_is_causal_decoding():

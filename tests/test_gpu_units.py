@@ -17,7 +17,11 @@ def _torch():
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 16, 32), (3, 48, 64), (8, 4608, 3584), (16, 896, 4864),
-                                   (5, 1000, 256), (8, 3584, 18944), (7, 2048, 128), (16, 32000, 896)])
+                                   (5, 1000, 256), (8, 3584, 18944), (7, 2048, 128), (16, 32000, 896),
+                                   # more than 16 rows: the tiled kernel (ragged rows, ragged
+                                   # feature tiles, split and unsplit K)
+                                   (17, 48, 64), (40, 1000, 256), (129, 1152, 896), (200, 320, 2048),
+                                   (256, 3584, 4864), (64, 37888, 512), (1000, 256, 160)])
 def test_linear_matches_fp64_matmul(M, N, K):
     """y = x W^T with bf16 weights; x is carried as bf16 head + tail, so the
     result must be fp32-accurate, far inside the 2e-3 budget."""
