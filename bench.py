@@ -180,6 +180,118 @@ def run_decode(args, cfg_id):
     return res
 
 
+MFMA_PEAK_TFLOPS = 2500.0
+
+
+def run_multi(args):
+    """Workload 4: the cfg2 model with 8 scenes, prefix 8192, 32 fields of 32-token
+    slots in a 4-level DAG, 4 given tokens per branch per step (multi-token masked
+    prefill inside each slot): 32 passes of 8 ready fields x 8 scenes x 4 tokens =
+    256 rows; with --stress one pass with all 32 fields active (1024 rows)."""
+    import torch
+    from paper_2602_02864_amd import Context, lib
+    from paper_2602_02864_amd.binding import _p, _check, _stream
+    from synth_inputs import model_dims, template
+    dims = model_dims(4)
+    tpl = template(4)
+    B, T, F, S = 8, 4, tpl.n_fields, tpl.slot_len[0]
+    R = F if args.stress else 8
+    ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T)
+    t0 = time.time()
+    build_model(ctx, dims, 2864004, torch)
+    log(f"[bench] model built in {time.time() - t0:.1f}s, "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    ctx.k_cache.normal_(generator=g)
+    ctx.v_cache.normal_(generator=g)
+    if args.stress:
+        # every field active at offset 0 although their ancestors are empty: not a
+        # state the scheduler produces, a kernel stress
+        passes = [(np.tile(np.arange(F, dtype=np.int32), B), np.full(B * F, 4 * j, dtype=np.int32))
+                  for j in range(S // T)]
+    else:
+        passes = [(np.tile(np.arange(8 * lv, 8 * lv + 8, dtype=np.int32), B),
+                   np.full(B * 8, 4 * j, dtype=np.int32)) for lv in range(F // 8) for j in range(S // T)]
+    M = B * R * T
+    gt = torch.Generator(device="cuda")
+    gt.manual_seed(5)
+    toks = torch.randint(0, dims.vocab, (len(passes), M), generator=gt, device="cuda", dtype=torch.int32)
+    tok_out = torch.empty(M, dtype=torch.int32, device="cuda")
+    L = lib()
+
+    def one(i):
+        p = i % len(passes)
+        if p == 0:
+            ctx.reset()
+        bf, bo = passes[p]
+        _check(L.fdc_parallel_decode_step(ctx._h, R, T, _p(bf), _p(bo), toks[p].data_ptr(), None,
+                                          tok_out.data_ptr(), None, None, None, _stream()))
+        return M
+
+    K = args.steps if args.steps > 0 else len(passes)
+    W = min(args.warmup, len(passes))
+    for i in range(W):
+        one(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tokens = 0
+    e0.record()
+    for i in range(K):
+        tokens += one(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    ctx.profile_enable(True)
+    for i in range(K):
+        one(i)
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    wb = weight_bytes(dims)
+    ov_ms = args.event_overhead_us * 1e-3
+    kernels = {}
+    gemm_flops, gemm_ms = 0.0, 0.0
+    for name, (kms, n) in prof.items():
+        if n == 0:
+            continue
+        avg = max(kms / n - ov_ms, 1e-6)
+        ent = {"avg_us": round(1e3 * avg, 2), "launches": n, "share": round(avg * n / ms, 4)}
+        if name in wb:
+            fl = 2.0 * M * wb[name] / 2                     # 2 * M * N * K
+            ent["TFLOP/s"] = round(fl / (avg * 1e-3) / 1e12, 1)
+            gemm_flops += fl * n
+            gemm_ms += avg * n
+        kernels[name] = ent
+    dom = "gate_up_swiglu"
+    dom_ms = max(prof[dom][0] / max(1, prof[dom][1]) - ov_ms, 1e-6)
+    fl = 2.0 * M * wb[dom] / 2
+    achieved = fl / (dom_ms * 1e-3) / 1e12
+    res = {
+        "metric": "CoT tokens/s in parallel decoding (given tokens, 4 per branch per step, batch 8)",
+        "value": round(tokens / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms / K, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg4{' all-active stress' if args.stress else ''}: {dims.n_layers}-layer "
+                               f"d={dims.d_model} {dims.n_q_heads}/{dims.n_kv_heads}x{dims.head_dim} "
+                               f"mlp={dims.d_mlp} vocab={dims.vocab}; prefix {tpl.prefix_len}; {F} fields x "
+                               f"{S}-token slots in 4 levels; batch {B}; {T} tokens per branch per step; "
+                               f"{R} branches = {M} rows per step; passes {len(passes)}"},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": MFMA_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
+                     "traffic": measured_traffic("cfg4", dom), "flops_per_launch": fl,
+                     "avg_us": round(dom_ms * 1e3, 2),
+                     "note": "achieved counts 2*M*N*K; the kernel issues twice that on the matrix cores "
+                             "(activations as bf16 head + tail)",
+                     "issued_frac": round(2 * achieved / MFMA_PEAK_TFLOPS, 4)},
+        "projections": {"TFLOP/s": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms else None,
+                        "share_of_step": round(gemm_ms / ms, 4)},
+        "kernels": kernels,
+    }
+    ctx.close()
+    return res
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch from the hardware counters (FETCH_SIZE + WRITE_SIZE,
     scaled by a copy of known size), as written by rocprof_summary.py from two
@@ -324,7 +436,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the workload's whole schedule)")
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg0", "cfg1", "cfg2", "cfg3"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--stress", action="store_true", help="cfg4: all 32 fields active (1024 rows per step)")
     ap.add_argument("--rho", type=float, default=0.3)
     ap.add_argument("--dag-seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -361,12 +474,15 @@ def main():
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a["frac"],
                             "traffic": measured_traffic("cfg3", "masked_attention")},
                "sweep": sweep}
+    elif args.workload == "cfg4":
+        res = run_multi(args)
+        args.no_cpu_baseline = True      # the oracle is timed on the default workload
     else:
         cfg_id = int(args.workload[3:])
         res = run_decode(args, cfg_id)
         if not args.no_attention:
             res["attention"] = run_attention(args, quick=True)
-    if not args.no_cpu_baseline and args.workload != "cfg3":
+    if not args.no_cpu_baseline and args.workload not in ("cfg3", "cfg4"):
         t0 = time.time()
         res["cpu_baseline"] = cpu_baseline(int(args.workload[3:]))
         log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")

@@ -1,14 +1,16 @@
 // Dense projections of the decode step for many rows (M > 16: several scenes,
 // several tokens per branch): y[M][N] = x[M][K] * W^T on the bf16 matrix cores.
 // Here the contraction itself is the bound, so the kernel is a tiled GEMM:
-//   * both operands already sit in memory in the operand order of
-//     v_mfma_f32_16x16x32_bf16 (weights: fdc_pack_weight; activations: the
-//     fragments the row kernels write), one 16 x 32 fragment = 1 KiB = one
-//     16-byte-per-lane load, so staging them through LDS needs no swizzle and
-//     has no bank conflicts;
+//   * both operands already sit in memory as 16 x 32 fragments of 1 KiB in
+//     matrix-instruction operand order (weights: fdc_pack_weight; activations:
+//     the fragments the row kernels write): one 16-byte-per-lane load each, so
+//     staging them through LDS needs no swizzle and has no bank conflicts;
 //   * a workgroup of 2 x 2 wavefronts owns 128 rows x (32 * NTW) features; each
 //     wavefront keeps a 64 x (16 * NTW) block of accumulators and feeds it from
 //     LDS (4 row fragments as bf16 head + tail, NTW weight fragments per k tile);
+//   * fragments go from memory through registers into a three-stage LDS ring,
+//     requested three k tiles ahead; one LDS-only barrier per k tile,
+//     across which the global loads stay in flight;
 //   * the activations keep their bf16 tail: two matrix instructions per weight
 //     fragment, fp32-accurate inputs;
 //   * K may be split over workgroups (partials summed by the consumer), and
@@ -21,20 +23,29 @@ namespace fdc {
 namespace {
 
 constexpr int kWgMTiles = 8;     // 16-row fragments per workgroup (2 wavefronts x 4)
+constexpr int kStages = 3;       // k tiles resident in LDS
+
+// Workgroup barrier that orders LDS traffic only: the global loads of the k
+// tile after next stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 template <int NTW, int EPI>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p) {
     constexpr int NF = 2 * kWgMTiles + 2 * NTW;        // fragments per k tile: rows (head, tail), weights
     constexpr int NLD = NF / 4;                        // ... fetched per wavefront
     static_assert(NF % 4 == 0, "fragments must divide over four wavefronts");
-    __shared__ uint4 lds[2][NF][64];
+    __shared__ uint4 lds[kStages][NF][64];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
 
     // workgroups that share a compute die (consecutive ids go round the eight
     // dies) take neighbouring tasks: the same weight columns for every row block
-    const int per_die = (gridDim.x + 7) / 8;
+    const int per_die = gridDim.x >> 3;
     const int task = (blockIdx.x & 7) * per_die + (blockIdx.x >> 3);
     if (task >= p.n_groups * p.m_blocks * p.S) return;
     const int mb = task % p.m_blocks;
@@ -43,97 +54,135 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
     const int kt0 = s * p.kt_split;
     const int nkt = min(p.KT, kt0 + p.kt_split) - kt0;
 
-    // the fragments this wavefront fetches each k tile
+    // The fragments this wavefront fetches each k tile; in LDS: the bf16 heads of
+    // the eight row fragments, their tails, then the weight fragments.  Fragments
+    // past the last row or feature tile re-read the last one: what they produce
+    // is never stored.
     const uint16_t* src[NLD];
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
         const int f = wave + 4 * j;
-        src[j] = nullptr;
         if (f < 2 * kWgMTiles) {
-            const int mt = mb * kWgMTiles + (f >> 1);
-            const uint16_t* base = (f & 1) ? a.act_lo : a.act_hi;
-            if (mt < p.m_tiles && base) src[j] = base + (((size_t)mt * p.KT + kt0) * 64 + lane) * 8;
+            const int mt = min(mb * kWgMTiles + (f & 7), p.m_tiles - 1);
+            src[j] = ((f >> 3) ? a.act_lo : a.act_hi) + (((size_t)mt * p.KT + kt0) * 64 + lane) * 8;
         } else {
-            const int tile = ng * 2 * NTW + (f - 2 * kWgMTiles);
-            if (tile < p.n_tiles) src[j] = a.w + (((size_t)tile * p.KT + kt0) * 64 + lane) * 8;
+            const int tile = min(ng * 2 * NTW + (f - 2 * kWgMTiles), p.n_tiles - 1);
+            src[j] = a.w + (((size_t)tile * p.KT + kt0) * 64 + lane) * 8;
         }
     }
+    // The contraction uses v_mfma_f32_32x32x16_bf16 (a single wavefront per SIMD
+    // keeps the matrix pipe full with it, which it does not with the 16x16x32
+    // form).  Its operand for 32 rows and one half of the k tile takes, from two
+    // neighbouring 16-row fragments, the 16-byte pieces
+    //   fragment (l % 32) / 16, piece l % 16 + 16 * (2 * half + l / 32)
+    // so the fragments stay as they are in memory and in LDS; only the LDS read
+    // address of a lane differs (16 consecutive lanes still read 256 contiguous
+    // bytes: no bank conflicts).
+    const int pair_off = ((lane & 31) >> 4) * 64 + (lane & 15) + 16 * (lane >> 5);   // in 16-byte units
+    constexpr int NB = NTW / 2;                         // 32-feature blocks per wavefront
+    f32x16 acc[2][NB];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[q][nb][e] = 0.f;
 
-    f32x4 acc[4][NTW];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NTW; ++ni) acc[mi][ni] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    uint4 stage[NLD];
-    auto fetch = [&](int i) {
-#pragma unroll
-        for (int j = 0; j < NLD; ++j) {
-            stage[j] = make_uint4(0, 0, 0, 0);
-            if (src[j]) stage[j] = *reinterpret_cast<const uint4*>(src[j] + (size_t)i * 512);
-        }
-    };
-    auto park = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < NLD; ++j) lds[buf][wave + 4 * j][lane] = stage[j];
-    };
-
+    // k tile i: memory -> registers -> ring stage.  Past the last tile the last
+    // one is fetched and parked again (into a stage nobody reads any more), so
+    // that every iteration is the same straight-line code.
+    f32x4 g0[NLD];
+#define FDC_FETCH(g, i)                                                                    \
+    _Pragma("unroll") for (int j = 0; j < NLD; ++j)                                        \
+        g[j] = *reinterpret_cast<const f32x4*>(src[j] + (size_t)min((i), nkt - 1) * 512)
+#define FDC_PARK(g, stg)                                                                   \
+    _Pragma("unroll") for (int j = 0; j < NLD; ++j)                                        \
+        *reinterpret_cast<f32x4*>(&lds[stg][wave + 4 * j][lane]) = g[j]
+    // Ring of three stages: while the matrix cores work on k tile i (stage
+    // i % 3), tile i+1 is resident, tile i+2 sits in the registers `g0` (fetched
+    // one iteration ago) and is parked at the end of the iteration into the
+    // stage tile i-1 occupied; tile i+3 is requested right after the barrier.
     if (nkt > 0) {
-        fetch(0);
-        park(0);
-    }
-    __syncthreads();
-    for (int i = 0; i < nkt; ++i) {
-        const int buf = i & 1;
-        if (i + 1 < nkt) fetch(i + 1);
-        bf16x8 ah[4], al[4];
+        FDC_FETCH(g0, 0);
+        FDC_PARK(g0, 0);
+        FDC_FETCH(g0, 1);
+        FDC_PARK(g0, 1);
+        FDC_FETCH(g0, 2);
+        lds_barrier();
+        int stg = 0;
+        for (int i = 0; i < nkt; ++i) {
+            const uint4* st = &lds[stg][0][0] + pair_off;
+            bf16x8 ah[2][2], al[2][2];                  // [32-row block][k half]
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-            ah[mi] = __builtin_bit_cast(bf16x8, lds[buf][2 * (wm * 4 + mi)][lane]);
-            al[mi] = __builtin_bit_cast(bf16x8, lds[buf][2 * (wm * 4 + mi) + 1][lane]);
-        }
+            for (int q = 0; q < 2; ++q)
 #pragma unroll
-        for (int ni = 0; ni < NTW; ++ni) {
-            const bf16x8 wv = __builtin_bit_cast(bf16x8, lds[buf][2 * kWgMTiles + wn * NTW + ni][lane]);
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, ah[mi], acc[mi][ni], 0, 0, 0);
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, al[mi], acc[mi][ni], 0, 0, 0);
-            }
-        }
-        if (i + 1 < nkt) park(buf ^ 1);
-        __syncthreads();
-    }
-
-    // accumulator register i of lane l: y[m = 16*mt + l%16][n = 16*tile + 4*(l/16) + i]
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        const int m = (mb * kWgMTiles + wm * 4 + mi) * 16 + (lane & 15);
-        if (m >= a.M) continue;
-        if (EPI == EPI_PARTIAL) {
-#pragma unroll
-            for (int ni = 0; ni < NTW; ++ni) {
-                const int n = (ng * 2 * NTW + wn * NTW + ni) * 16 + 4 * (lane >> 4);
-                if (n < a.n_valid)
-                    *reinterpret_cast<f32x4*>(a.out + ((size_t)s * a.M + m) * a.N + n) = acc[mi][ni];
-            }
-        } else {   // tiles alternate: gate rows, up rows of the same 16 features
-#pragma unroll
-            for (int ni = 0; ni < NTW; ni += 2) {
-                const int ftile = (ng * 2 * NTW + wn * NTW + ni) >> 1;
-                if (2 * ftile + 1 >= p.n_tiles) continue;
-                const f32x4 g = acc[mi][ni], u = acc[mi][ni + 1];
-                uint16_t hi[4], lo[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float h = g[e] / (1.0f + __expf(-g[e])) * u[e];
-                    split_bf16(h, hi[e], lo[e]);
+                for (int h = 0; h < 2; ++h) {
+                    ah[q][h] = __builtin_bit_cast(bf16x8, st[(4 * wm + 2 * q) * 64 + 32 * h]);
+                    al[q][h] = __builtin_bit_cast(bf16x8, st[(8 + 4 * wm + 2 * q) * 64 + 32 * h]);
                 }
-                const size_t o = act_frag_index(m, ftile * 16 + 4 * (lane >> 4), a.out_KT);
-                *reinterpret_cast<uint2*>(a.out_hi + o) =
-                    make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
-                *reinterpret_cast<uint2*>(a.out_lo + o) =
-                    make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                bf16x8 wv[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    wv[h] = __builtin_bit_cast(bf16x8, st[(2 * kWgMTiles + wn * NTW + 2 * nb) * 64 + 32 * h]);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], ah[q][h], acc[q][nb], 0, 0, 0);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], al[q][h], acc[q][nb], 0, 0, 0);
+            }
+            const int into = stg == 0 ? 2 : stg - 1;           // (i + 2) % 3
+            FDC_PARK(g0, into);
+            lds_barrier();
+            FDC_FETCH(g0, i + 3);
+            stg = stg == 2 ? 0 : stg + 1;
+        }
+    }
+#undef FDC_FETCH
+#undef FDC_PARK
+
+    // accumulator register e of lane l in block (q, nb):
+    //   y[m = 32 * (row block) + l % 32][n = 32 * (feature block) + 8 * (e / 4) + 4 * (l / 32) + e % 4]
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int m = (mb * kWgMTiles + wm * 4 + 2 * q) * 16 + (lane & 31);
+        if (m >= a.M) continue;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int tile0 = ng * 2 * NTW + wn * NTW + 2 * nb;      // first of the block's two 16-feature tiles
+            if (EPI == EPI_PARTIAL) {
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const int n = tile0 * 16 + 8 * e4 + 4 * (lane >> 5);
+                    if (n < a.n_valid) {
+                        const f32x4 v = {acc[q][nb][4 * e4], acc[q][nb][4 * e4 + 1], acc[q][nb][4 * e4 + 2],
+                                         acc[q][nb][4 * e4 + 3]};
+                        *reinterpret_cast<f32x4*>(a.out + ((size_t)s * a.M + m) * a.N + n) = v;
+                    }
+                }
+            } else {   // the block's first tile holds the gate rows, its second the up rows of 16 features
+                if (tile0 + 1 >= p.n_tiles) continue;
+                const int ftile = tile0 >> 1;
+#pragma unroll
+                for (int e4 = 0; e4 < 2; ++e4) {
+                    uint16_t hi[4], lo[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gt = acc[q][nb][4 * e4 + e], up = acc[q][nb][8 + 4 * e4 + e];
+                        split_bf16(gt / (1.0f + __expf(-gt)) * up, hi[e], lo[e]);
+                    }
+                    const size_t o = act_frag_index(m, ftile * 16 + 8 * e4 + 4 * (lane >> 5), a.out_KT);
+                    *reinterpret_cast<uint2*>(a.out_hi + o) =
+                        make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
+                    *reinterpret_cast<uint2*>(a.out_lo + o) =
+                        make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+                }
             }
         }
     }
