@@ -91,59 +91,65 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
     // k tile i: memory -> registers -> ring stage.  Past the last tile the last
     // one is fetched and parked again (into a stage nobody reads any more), so
     // that every iteration is the same straight-line code.
-    f32x4 g0[NLD];
+    f32x4 g0[NLD], g1[NLD];
 #define FDC_FETCH(g, i)                                                                    \
     _Pragma("unroll") for (int j = 0; j < NLD; ++j)                                        \
         g[j] = *reinterpret_cast<const f32x4*>(src[j] + (size_t)min((i), nkt - 1) * 512)
 #define FDC_PARK(g, stg)                                                                   \
     _Pragma("unroll") for (int j = 0; j < NLD; ++j)                                        \
         *reinterpret_cast<f32x4*>(&lds[stg][wave + 4 * j][lane]) = g[j]
-    // Ring of three stages: while the matrix cores work on k tile i (stage
-    // i % 3), tile i+1 is resident, tile i+2 sits in the registers `g0` (fetched
-    // one iteration ago) and is parked at the end of the iteration into the
-    // stage tile i-1 occupied; tile i+3 is requested right after the barrier.
+    // the matrix work of one k tile out of ring stage `stg`
+#define FDC_MMA(stg)                                                                                  \
+    {                                                                                                 \
+        const uint4* st = &lds[stg][0][0] + pair_off;                                                 \
+        bf16x8 ah[2][2], al[2][2]; /* [32-row block][k half] */                                       \
+        _Pragma("unroll") for (int q = 0; q < 2; ++q)                                                 \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                               \
+            ah[q][h] = __builtin_bit_cast(bf16x8, st[(4 * wm + 2 * q) * 64 + 32 * h]);                \
+            al[q][h] = __builtin_bit_cast(bf16x8, st[(8 + 4 * wm + 2 * q) * 64 + 32 * h]);            \
+        }                                                                                             \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                           \
+            bf16x8 wv[2];                                                                             \
+            _Pragma("unroll") for (int h = 0; h < 2; ++h)                                             \
+                wv[h] = __builtin_bit_cast(bf16x8, st[(2 * kWgMTiles + wn * NTW + 2 * nb) * 64 + 32 * h]); \
+            _Pragma("unroll") for (int h = 0; h < 2; ++h)                                             \
+            _Pragma("unroll") for (int q = 0; q < 2; ++q)                                             \
+                acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], ah[q][h], acc[q][nb], 0, 0, 0); \
+            _Pragma("unroll") for (int h = 0; h < 2; ++h)                                             \
+            _Pragma("unroll") for (int q = 0; q < 2; ++q)                                             \
+                acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], al[q][h], acc[q][nb], 0, 0, 0); \
+        }                                                                                             \
+    }
+    // One iteration.  Tile i+2 (requested two iterations ago into `g`) goes
+    // into the ring stage tile i-1 occupied, tile i+4 is requested into `g`,
+    // and the matrix cores work on k tile i (stage i % 3); the LDS writes and the
+    // global loads run under the matrix instructions.  One LDS-only barrier.
+#define FDC_ITER(g, i)                                                                     \
+    {                                                                                      \
+        const int into = stg == 0 ? 2 : stg - 1; /* (i + 2) % 3 */                         \
+        FDC_PARK(g, into);                                                                 \
+        FDC_FETCH(g, (i) + 4);                                                             \
+        FDC_MMA(stg);                                                                      \
+        lds_barrier();                                                                     \
+        stg = stg == 2 ? 0 : stg + 1;                                                      \
+    }
     if (nkt > 0) {
         FDC_FETCH(g0, 0);
+        FDC_FETCH(g1, 1);
         FDC_PARK(g0, 0);
-        FDC_FETCH(g0, 1);
-        FDC_PARK(g0, 1);
         FDC_FETCH(g0, 2);
+        FDC_PARK(g1, 1);
+        FDC_FETCH(g1, 3);
         lds_barrier();
-        int stg = 0;
-        for (int i = 0; i < nkt; ++i) {
-            const uint4* st = &lds[stg][0][0] + pair_off;
-            bf16x8 ah[2][2], al[2][2];                  // [32-row block][k half]
-#pragma unroll
-            for (int q = 0; q < 2; ++q)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    ah[q][h] = __builtin_bit_cast(bf16x8, st[(4 * wm + 2 * q) * 64 + 32 * h]);
-                    al[q][h] = __builtin_bit_cast(bf16x8, st[(8 + 4 * wm + 2 * q) * 64 + 32 * h]);
-                }
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                bf16x8 wv[2];
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    wv[h] = __builtin_bit_cast(bf16x8, st[(2 * kWgMTiles + wn * NTW + 2 * nb) * 64 + 32 * h]);
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-                        acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], ah[q][h], acc[q][nb], 0, 0, 0);
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-                        acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], al[q][h], acc[q][nb], 0, 0, 0);
-            }
-            const int into = stg == 0 ? 2 : stg - 1;           // (i + 2) % 3
-            FDC_PARK(g0, into);
-            lds_barrier();
-            FDC_FETCH(g0, i + 3);
-            stg = stg == 2 ? 0 : stg + 1;
+        int stg = 0, i = 0;
+        for (; i + 1 < nkt; i += 2) {
+            FDC_ITER(g0, i);
+            FDC_ITER(g1, i + 1);
         }
+        if (i < nkt) FDC_MMA(stg);
     }
+#undef FDC_ITER
+#undef FDC_MMA
 #undef FDC_FETCH
 #undef FDC_PARK
 
