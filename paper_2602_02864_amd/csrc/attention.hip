@@ -436,13 +436,19 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     __shared__ uint32_t tile_any[kMaxMaskedTiles];
     __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
     __shared__ int s_start[kMaxFields];
-    __shared__ uint16_t act_list[kMaxChunkTiles];
+    __shared__ uint16_t act_list[kMaxChunkTilesReg];
     __shared__ int n_act_sh;
     __shared__ float red_m[4][NR], red_l[4][NR];
     __shared__ f32x4 red_o[NRT * DT * 4 * 64];
     __shared__ bf16x8 qlo[QF32 ? NRT * DJ * 64 : 1];
 
-    const int chunk = blockIdx.x, rg = blockIdx.y, z = blockIdx.z;
+    // Row groups of the same (scene, KV head, chunk) read the same tiles: they
+    // get consecutive ids on one compute die (launch ids go round the eight
+    // dies), so that one fetch from memory serves them all through that die's L2.
+    const int n_wg = gridDim.x * gridDim.y * gridDim.z;
+    int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    if ((n_wg & 7) == 0) lin = (lin & 7) * (n_wg >> 3) + (lin >> 3);
+    const int rg = lin % a.n_rg, chunk = (lin / a.n_rg) % a.n_chunks, z = lin / (a.n_rg * a.n_chunks);
     const int b = z / a.Hkv, kvh = z % a.Hkv;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int r32 = lane & 31, hh = lane >> 5;
@@ -503,7 +509,7 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     __syncthreads();
     if (wave == 0) {
         int base = 0;
-        for (int c0 = 0; c0 < a.CB; c0 += 64) {               // CB <= kMaxChunkTiles
+        for (int c0 = 0; c0 < a.CB; c0 += 64) {               // CB <= kMaxChunkTilesReg
             const int blk = cb0 + c0 + lane;
             bool actv = blk < blk_end;
             if (actv && blk >= mt0) actv = tile_any[blk - mt0] != 0u;
@@ -582,24 +588,29 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
                     for (int dt = 0; dt < DT; ++dt) vf[dt][s].u[k] &= wm;
                 }
         }
+        // scores of every row tile first: the matrix pipe then has work queued
+        // while the vector ALUs run the softmax of the first row tile
+        f32x16 sc[NRT];
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) sc[rt][k] = 0.f;
+#pragma unroll
+            for (int j = 0; j < DJ; ++j) {
+                sc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qh[rt][j].v, sc[rt], 0, 0, 0);
+                if (QF32)
+                    sc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qlo[(rt * DJ + j) * 64 + lane], sc[rt], 0, 0, 0);
+            }
+        }
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt) {
             uint32_t vbits = 0xffffu;
             if (MASKED) vbits = lane_bits(rowmask[blk - mt0][rt * 32 + r32], hh);
-            f32x16 sc;
-#pragma unroll
-            for (int k = 0; k < 16; ++k) sc[k] = 0.f;
-#pragma unroll
-            for (int j = 0; j < DJ; ++j) {
-                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qh[rt][j].v, sc, 0, 0, 0);
-                if (QF32)
-                    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j].v, qlo[(rt * DJ + j) * 64 + lane], sc, 0, 0, 0);
-            }
             float mx = kNegBig;
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                if (MASKED) sc[k] = (vbits >> k & 1u) ? sc[k] : kNegBig;
-                mx = fmaxf(mx, sc[k]);
+                if (MASKED) sc[rt][k] = (vbits >> k & 1u) ? sc[rt][k] : kNegBig;
+                mx = fmaxf(mx, sc[rt][k]);
             }
             mx = fmaxf(mx, other_half(mx, hh));
             const float m_new = fmaxf(m_run[rt], mx * a.scale_log2);
@@ -609,7 +620,7 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
             float p[16];
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                p[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[k], a.scale_log2, -m_new));
+                p[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[rt][k], a.scale_log2, -m_new));
                 if (MASKED) p[k] = (vbits >> k & 1u) ? p[k] : 0.f;
                 psum += p[k];
             }
@@ -620,12 +631,11 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
                     split2(p[8 * s + 2 * k], p[8 * s + 2 * k + 1], ph[s].u[k], pl[s].u[k]);
-            if (__any(alpha != 1.0f)) {
+            // unconditional: a branch here would cut the tile into scheduling regions
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) o[rt][dt][k] *= alpha;
-            }
+                for (int k = 0; k < 16; ++k) o[rt][dt][k] *= alpha;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll

@@ -116,15 +116,32 @@ void plan_attention(fdc_ctx* c) {
     c->attn_variant = large ? 1 : 0;
     long want_wgs = (large ? 256L : 64L) * (c->m.head_dim == 128 ? 1 : 2);
     if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
-    long chunks = std::max(1L, (want_wgs + zr / 2) / zr);
-    long cb = (c->NB + chunks - 1) / chunks;
-    cb = std::max(4L, (cb + 1) / 2 * 2);
-    cb = std::min(cb, (long)kMaxChunkTiles);
+    if (const char* e = std::getenv("FDC_ATTN_VARIANT")) c->attn_variant = std::atoi(e) == 1 ? 1 : 0;
     const long masked_total = c->NB - c->P / 32;
+    long cb;
+    if (c->attn_variant == 1 && !std::getenv("FDC_ATTN_WGS")) {
+        // whole rounds of workgroups over the compute units: the cheapest of
+        // (rounds) x (tiles per chunk + a fixed set-up and merge cost)
+        long best = 0, best_cost = 0;
+        for (long ch = 1; ch <= std::max(1L, (long)c->NB / 8); ++ch) {
+            const long t = (c->NB + ch - 1) / ch;
+            if (t > kMaxChunkTilesReg) continue;
+            const long cost = ((zr * ch + 255) / 256) * (t + 6);
+            if (best == 0 || cost < best_cost) {
+                best = ch;
+                best_cost = cost;
+            }
+        }
+        cb = best ? (c->NB + best - 1) / best : kMaxChunkTilesReg;
+    } else {
+        const long chunks = std::max(1L, (want_wgs + zr / 2) / zr);
+        cb = (c->NB + chunks - 1) / chunks;
+        cb = std::max(4L, (cb + 1) / 2 * 2);
+        cb = std::min(cb, (long)(c->attn_variant == 1 ? kMaxChunkTilesReg : kMaxChunkTiles));
+    }
     if (masked_total > kMaxMaskedTiles) cb = std::min(cb, (long)kMaxMaskedTiles);
     c->attn_cb = (int)cb;
     c->attn_chunks = (int)((c->NB + cb - 1) / cb);
-    if (const char* e = std::getenv("FDC_ATTN_VARIANT")) c->attn_variant = std::atoi(e) == 1 ? 1 : 0;
 }
 
 size_t carve(fdc_ctx* c) {

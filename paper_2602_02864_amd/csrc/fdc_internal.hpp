@@ -18,7 +18,8 @@ constexpr int kMaxFields = 64;      // one 64-bit ancestor word per field in the
 constexpr int kMaxRowsDense = 16;   // rows per step the streaming projections take; more go to the tiled ones
 constexpr int kMaxRowsStep = 1024;  // rows per step overall
 constexpr int kStageSlots = 8;      // pinned staging ring for per-step metadata
-constexpr int kMaxChunkTiles = 128; // 32-key tiles one attention workgroup walks at most
+constexpr int kMaxChunkTiles = 128; // 32-key tiles one attention workgroup walks at most (LDS-shared tiles)
+constexpr int kMaxChunkTilesReg = 512;  // ... with tiles in registers
 constexpr int kMaxMaskedTiles = 32; // ... of which this many may reach into the slots
 
 // How one projection y = x W^T is cut: S splits of the reduction dimension,
