@@ -334,7 +334,6 @@ TiledPlan plan_tiled(int M, int64_t n_out, int64_t k_in, bool swiglu, int max_sp
                 best.grid = (int)((tasks + 7) / 8 * 8);
             }
         }
-    if (const char* e = std::getenv("FDC_GEMM_DBG")) best.dbg = std::atoi(e);
     return best;
 }
 

@@ -51,7 +51,6 @@ struct TiledPlan {
     int n_groups = 0;  // workgroup columns
     int m_blocks = 0;  // workgroup rows
     int grid = 0;
-    int dbg = 0;
 };
 
 TiledPlan plan_tiled(int M, int64_t n_out, int64_t k_in, bool swiglu, int max_splits = 16);
