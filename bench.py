@@ -188,6 +188,23 @@ def run_decode(args, cfg_id, chain=False):
         "kernels": kernels,
         "host_wall_ms_per_step": round(1e3 * t_wall / K, 4),
     }
+    if args.prefill:
+        # the prefix as field 0 of a context over the same cache: causal prefill by
+        # the same step, `chunk` embedding rows per pass (the paper's "CoT time" also
+        # counts this input processing, Sec. 4.1; the decode figure above does not)
+        chunk, P = 128, tpl.prefix_len
+        view = ctx.prefill_view(chunk)
+        emb = torch.randn(1, P, dims.d_model, device=dev, generator=g).to(torch.bfloat16)
+        for rep in range(2):
+            view.reset()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            view.prefill(emb, chunk)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+        res["prefill"] = {"tokens": P, "chunk": chunk, "ms": round(1e3 * dt, 2),
+                          "tokens_per_s": round(P / dt, 1)}
+        view.close()
     ctx.close()
     return res
 
@@ -455,6 +472,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-ar", action="store_true", help="skip the autoregressive (chain graph) baseline")
+    ap.add_argument("--prefill", action="store_true", help="also time the causal prefill of the prefix")
     ap.add_argument("--single", action="store_true", help="cfg3: only --rho, no sweep over densities")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

@@ -275,7 +275,9 @@ class Context:
     packed weights).  Methods carry the names of the C entry points."""
 
     def __init__(self, dims, slot_len, edges, prefix_len, n_scenes=1, max_branches=1, max_tokens=1,
-                 device="cuda:0"):
+                 device="cuda:0", share=None):
+        """share: another Context over the same model and the same cache positions
+        (same total length) whose KV cache and packed weights this one uses too."""
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -290,14 +292,56 @@ class Context:
         _check(lib().fdc_create(C.byref(self.desc), self.F, _p(self.slot_len), src.size, _p(src), _p(dst),
                                 int(prefix_len), n_scenes, max_branches, max_tokens, C.byref(self._h)))
         self._keep = []
+        self._layer_w, self._head_w = {}, None
+        self.edges = [(int(u), int(v)) for u, v in zip(src, dst)]
+        self.prefix_len = int(prefix_len)
         with torch.cuda.device(self.device):
             kvb = int(lib().fdc_kv_cache_bytes(self._h))
-            self.k_cache = torch.zeros(kvb // 2, dtype=torch.bfloat16, device=self.device)
-            self.v_cache = torch.zeros(kvb // 2, dtype=torch.bfloat16, device=self.device)
+            if share is not None:
+                if share.k_cache.numel() * 2 != kvb:
+                    raise ValueError("contexts that share a cache must cover the same positions")
+                self.k_cache, self.v_cache = share.k_cache, share.v_cache
+            else:
+                self.k_cache = torch.zeros(kvb // 2, dtype=torch.bfloat16, device=self.device)
+                self.v_cache = torch.zeros(kvb // 2, dtype=torch.bfloat16, device=self.device)
             _check(lib().fdc_set_kv_cache(self._h, self.k_cache.data_ptr(), self.v_cache.data_ptr()))
             wsb = int(lib().fdc_workspace_bytes(self._h))
             self.workspace = torch.empty(wsb, dtype=torch.uint8, device=self.device)
             _check(lib().fdc_set_workspace(self._h, self.workspace.data_ptr(), wsb, _stream()))
+        if share is not None:
+            for layer, lw in share._layer_w.items():
+                _check(lib().fdc_set_layer_weights(self._h, layer, C.byref(lw)))
+                self._layer_w[layer] = lw
+            if share._head_w is not None:
+                _check(lib().fdc_set_head_weights(self._h, *share._head_w))
+                self._head_w = share._head_w
+            self._keep.append(share._keep)
+
+    def prefill_view(self, max_tokens: int):
+        """A context over the same cache and weights in which the prefix is field 0
+        (a slot of prefix_len tokens that every other field depends on): stepping
+        field 0 with T tokens per pass is the causal prefill of the prefix, a
+        multi-token masked prefill inside a slot like any other (Sec. 3.3)."""
+        P = self.prefix_len
+        if P < 1:
+            raise ValueError("no prefix to prefill")
+        edges = [(0, f + 1) for f in range(self.F)] + [(u + 1, v + 1) for u, v in self.edges]
+        return Context(self.dims, [P] + [int(x) for x in self.slot_len], edges, 0, self.B, 1, max_tokens,
+                       device=str(self.device), share=self)
+
+    def prefill(self, emb_rows, chunk: int):
+        """Causal prefill of field 0 of every scene from embedding rows [B][n][d]
+        (bf16 values), `chunk` tokens per pass; returns the last pass's outputs."""
+        torch = self.torch
+        e = self._dev_bf16(emb_rows).reshape(self.B, -1, self.dims.d_model)
+        n = e.shape[1]
+        out = None
+        for t0 in range(0, n, chunk):
+            T = min(chunk, n - t0)
+            out = self.parallel_decode_step(np.zeros((self.B, 1), dtype=np.int32),
+                                            np.full((self.B, 1), t0, dtype=np.int32),
+                                            emb_in=e[:, t0:t0 + T].contiguous(), T=T, want_hidden=True)
+        return out
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:
@@ -340,12 +384,14 @@ class Context:
         lw = LayerWeights(g1.data_ptr(), packed["wqkv"].data_ptr(), packed["wo"].data_ptr(),
                           g2.data_ptr(), packed["wgu"].data_ptr(), packed["wd"].data_ptr())
         _check(lib().fdc_set_layer_weights(self._h, layer, C.byref(lw)))
+        self._layer_w[layer] = lw
         self._keep.append((g1, g2, packed))
 
     def set_head_weights(self, emb, gf, lm):
         e, g = self._dev_bf16(emb), self._dev_f32(gf)
         lmp = fdc_pack_weight(self._dev_bf16(lm))
-        _check(lib().fdc_set_head_weights(self._h, e.data_ptr(), g.data_ptr(), lmp.data_ptr()))
+        self._head_w = (e.data_ptr(), g.data_ptr(), lmp.data_ptr())
+        _check(lib().fdc_set_head_weights(self._h, *self._head_w))
         self._keep.append((e, g, lmp))
 
     # -- state ---------------------------------------------------------------------

@@ -10,7 +10,7 @@ import oracle.fdc_oracle as O
 from synth_inputs import (ModelDims, bf16_round, chain_template, draw_layer_weights,
                           draw_normal_bf16, draw_prefix_embeddings, draw_tokens, draw_weights,
                           model_dims, random_dag_template, template, workload_seed)
-from tests.helpers import Pair, rel_err, run_schedule
+from tests.helpers import HIDDEN_TOL, Pair, rel_err, run_schedule
 
 pytestmark = pytest.mark.gpu
 
@@ -93,6 +93,48 @@ def test_many_rows_per_step_use_the_tiled_projections(seed, B, T, R, Hq, Hkv, D,
     dims = ModelDims(n_layers=2, d_model=Hq * 32, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, d_mlp=352,
                      vocab=600 + 4 * seed)
     assert _random_model_steps(seed, B, T, R, dims, n_fields=F, max_slot=12, n_steps=5) >= 2
+
+
+@pytest.mark.parametrize("seed,B,P,chunk,D", [(30, 1, 70, 16, 64), (31, 2, 45, 32, 128)])
+def test_prefix_prefill_through_the_step(seed, B, P, chunk, D):
+    """The prefix as field 0 of a context over the same cache: stepping it with
+    `chunk` tokens per pass is the causal prefill.  Its final hidden rows match the
+    oracle's plain causal pass, and decoding on top of the prefilled cache matches
+    the oracle decoding on top of its own prefill."""
+    dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=D, d_mlp=160, vocab=520)
+    tpl = random_dag_template(900 + seed, n_fields=4, prefix_len=P, max_slot=8, edge_prob=0.5, vocab=dims.vocab)
+    w = draw_weights(10 + seed, dims, random_gains=True, std=0.05)
+    pair = Pair(dims, tpl, w, n_scenes=B, max_branches=tpl.n_fields)
+    view = pair.ctx.prefill_view(max_tokens=chunk)
+    emb = np.stack([draw_prefix_embeddings(10 + seed, P, dims.d_model, extra=b) for b in range(B)])
+    emb = bf16_round(emb.astype(np.float32))
+    out = view.prefill(emb, chunk)
+    import torch
+    torch.cuda.synchronize()
+    last = min(chunk, P - (P - 1) // chunk * chunk)          # rows of the last pass
+    hid = out["hidden"].cpu().numpy()[dims.n_layers].reshape(B, last, dims.d_model)
+    for b in range(B):
+        x = pair.dec.prefill_prefix(b, emb[b])
+        assert rel_err(hid[b], x[P - last:]) <= HIDDEN_TOL
+    # the cache is bf16 storage on both sides
+    pair.dec.K[:, :, :, :P] = bf16_round(pair.dec.K[:, :, :, :P].astype(np.float32))
+    pair.dec.V[:, :, :, :P] = bf16_round(pair.dec.V[:, :, :, :P].astype(np.float32))
+    assert list(view.get_valid_len()[:, 0]) == [P] * B
+    roots = [f for f in range(tpl.n_fields) if not any(v == f for _, v in tpl.edges)]
+    rng = np.random.default_rng(seed)
+    for step in range(3):
+        bf = np.full((B, tpl.n_fields), -1, dtype=np.int32)
+        bo = np.zeros((B, tpl.n_fields), dtype=np.int32)
+        for b in range(B):
+            for i, f in enumerate(roots):
+                if step < tpl.slot_len[f]:
+                    bf[b, i], bo[b, i] = f, step
+        if (bf < 0).all():
+            break
+        tok = rng.integers(0, dims.vocab, size=(B, tpl.n_fields, 1)).astype(np.int32)
+        pair.step_both(bf, bo, tok, tag=f"after prefill, step {step}")
+    view.close()
+    pair.close()
 
 
 def test_chain_dag_on_gpu_is_causal_decoding():
