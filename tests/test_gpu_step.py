@@ -184,6 +184,29 @@ def test_workload2_shapes_two_layers():
     pair.close()
 
 
+def test_workload4_shapes_one_layer_256_rows():
+    """Workload-4 shapes at full width (7B-class layer, 8 scenes, prefix 8192, 32 fields
+    of 32-token slots in 4 levels, 4 tokens per branch per pass = 256 rows): the tiled
+    projections and four row groups per KV head in the launch shape the benchmark
+    times; one pass of the first level on one layer (the oracle's cost)."""
+    dims = model_dims(4, n_layers=1)
+    tpl = template(4)
+    w = {"layers": [draw_layer_weights(4, dims, 0, random_gains=True)]}
+    rng = workload_seed(4, "weights", 0)
+    w["emb"] = draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)
+    w["gf"] = draw_normal_bf16(rng, (dims.d_model,), 0.02, 1.0)
+    w["lm"] = draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)
+    B, R, T = 8, 8, 4
+    pair = Pair(dims, tpl, w, n_scenes=B, max_branches=R, max_tokens=T)
+    for b in range(B):
+        _random_prefix_kv(pair, 4, scene=b)
+    trng = np.random.default_rng(44)
+    bf = np.tile(np.arange(R, dtype=np.int32), (B, 1))
+    tok = trng.integers(0, dims.vocab, size=(B, R, T)).astype(np.int32)
+    pair.step_both(bf, np.zeros((B, R), dtype=np.int32), tok, T=T, tag="cfg4 level 0")
+    pair.close()
+
+
 def test_step_error_paths_leave_state_unchanged():
     from paper_2602_02864_amd import FdcError, binding as fb
     dims = model_dims(0)
