@@ -22,16 +22,17 @@ __device__ __forceinline__ float block_sum(float v, float* sh) {
 }
 
 // One workgroup per row.  x <- (embedding | x + sum of partials); a <- rmsnorm(x) * gain.
-// Every thread owns up to kNormVec groups of four consecutive columns and issues
-// all of its loads before it touches any of them: the kernel is one round trip
-// to memory, one block reduction and one round of stores.
-constexpr int kNormVec = 5;                                  // 256 threads * 4 * 5 = d_model <= 5120
-__global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a, StepMeta sm) {
-    __shared__ float sh[4];
+// Every thread owns VEC groups of four consecutive columns (one at d_model <=
+// 4096: NT = 1024 threads) and issues the loads of up to eight split-K
+// partials before it adds any of them (in split order): the kernel is one or two
+// round trips to memory, one block reduction and one round of stores.
+template <int NT, int VEC>
+__global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm) {
+    __shared__ float sh[NT / 64];
     const int m = blockIdx.x;
     const bool active = sm.branch_field == nullptr || sm.branch_field[m / sm.T] >= 0;
     const int nvec = a.d >> 2;
-    f32x4 v[kNormVec];
+    f32x4 v[VEC];
     const float* __restrict__ xin = a.x + (size_t)m * a.d;
     const float* __restrict__ part = a.part;
     const uint16_t* __restrict__ erow = nullptr;
@@ -43,8 +44,8 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a, StepMeta sm
         erow = a.emb_rows + (size_t)m * a.d;
     }
 #pragma unroll
-    for (int i = 0; i < kNormVec; ++i) {
-        const int q = threadIdx.x + i * 256;
+    for (int i = 0; i < VEC; ++i) {
+        const int q = threadIdx.x + i * NT;
         v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (q < nvec && active) {
             if (erow) {
@@ -57,27 +58,34 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a, StepMeta sm
         }
     }
     if (!erow && active) {
-        for (int s = 0; s < a.S; ++s) {
-            f32x4 p[kNormVec];
+        for (int s0 = 0; s0 < a.S; s0 += 8) {
+            f32x4 p[8][VEC];
 #pragma unroll
-            for (int i = 0; i < kNormVec; ++i) {
-                const int q = threadIdx.x + i * 256;
-                p[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (q < nvec) p[i] = *reinterpret_cast<const f32x4*>(part + ((size_t)s * a.M + m) * a.d + 4 * q);
+            for (int j = 0; j < 8; ++j) {
+                const int s = min(s0 + j, a.S - 1);            // past the end: a repeat, not added
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    const int q = threadIdx.x + i * NT;
+                    p[j][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (q < nvec) p[j][i] = *reinterpret_cast<const f32x4*>(part + ((size_t)s * a.M + m) * a.d + 4 * q);
+                }
             }
 #pragma unroll
-            for (int i = 0; i < kNormVec; ++i) v[i] += p[i];
+            for (int j = 0; j < 8; ++j)
+                if (s0 + j < a.S)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) v[i] += p[j][i];
         }
     }
     float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < kNormVec; ++i) ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
+    for (int i = 0; i < VEC; ++i) ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
     const float tot = block_sum(ss, sh);
     const float rstd = rsqrtf(tot / (float)a.d + a.eps);
     const int KT = a.d >> 5;
 #pragma unroll
-    for (int i = 0; i < kNormVec; ++i) {
-        const int q = threadIdx.x + i * 256;
+    for (int i = 0; i < VEC; ++i) {
+        const int q = threadIdx.x + i * NT;
         if (q >= nvec) continue;
         const int k = 4 * q;
         *reinterpret_cast<f32x4*>(a.x + (size_t)m * a.d + k) = v[i];
@@ -260,7 +268,10 @@ void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st
 }
 
 void launch_resid_norm(const NormArgs& a, const StepMeta& sm, hipStream_t st) {
-    hipLaunchKernelGGL(resid_norm_kernel, dim3(a.M), dim3(256), 0, st, a, sm);
+    const int nvec = a.d / 4;                       // d_model <= 8192
+    if (nvec <= 256) hipLaunchKernelGGL((resid_norm_kernel<256, 1>), dim3(a.M), dim3(256), 0, st, a, sm);
+    else if (nvec <= 1024) hipLaunchKernelGGL((resid_norm_kernel<1024, 1>), dim3(a.M), dim3(1024), 0, st, a, sm);
+    else hipLaunchKernelGGL((resid_norm_kernel<1024, 2>), dim3(a.M), dim3(1024), 0, st, a, sm);
 }
 
 void launch_rope_table(const double* inv_freq, float2* tab, int n_pos, int half, hipStream_t st) {
