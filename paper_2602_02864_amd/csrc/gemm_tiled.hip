@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
     // k tile i: memory -> registers -> ring stage.  Past the last tile the last
     // one is fetched and parked again (into a stage nobody reads any more), so
     // that every iteration is the same straight-line code.
-    f32x4 g0[NLD], g1[NLD];
+    f32x4 g0[NLD], g1[NLD], g2[NLD];
 #define FDC_FETCH(g, i)                                                                    \
     _Pragma("unroll") for (int j = 0; j < NLD; ++j)                                        \
         g[j] = *reinterpret_cast<const f32x4*>(src[j] + (size_t)min((i), nkt - 1) * 512)
@@ -120,15 +120,15 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
                 acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], al[q][h], acc[q][nb], 0, 0, 0); \
         }                                                                                             \
     }
-    // One iteration.  Tile i+2 (requested two iterations ago into `g`) goes
-    // into the ring stage tile i-1 occupied, tile i+4 is requested into `g`,
+    // One iteration.  Tile i+2 (requested three iterations ago into `g`) goes
+    // into the ring stage tile i-1 occupied, tile i+5 is requested into `g`,
     // and the matrix cores work on k tile i (stage i % 3); the LDS writes and the
     // global loads run under the matrix instructions.  One LDS-only barrier.
 #define FDC_ITER(g, i)                                                                     \
     {                                                                                      \
         const int into = stg == 0 ? 2 : stg - 1; /* (i + 2) % 3 */                         \
         FDC_PARK(g, into);                                                                 \
-        FDC_FETCH(g, (i) + 4);                                                             \
+        FDC_FETCH(g, (i) + 5);                                                             \
         FDC_MMA(stg);                                                                      \
         lds_barrier();                                                                     \
         stg = stg == 2 ? 0 : stg + 1;                                                      \
@@ -136,15 +136,21 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
     if (nkt > 0) {
         FDC_FETCH(g0, 0);
         FDC_FETCH(g1, 1);
+        FDC_FETCH(g2, 2);
         FDC_PARK(g0, 0);
-        FDC_FETCH(g0, 2);
+        FDC_FETCH(g0, 3);
         FDC_PARK(g1, 1);
-        FDC_FETCH(g1, 3);
+        FDC_FETCH(g1, 4);
         lds_barrier();
         int stg = 0, i = 0;
-        for (; i + 1 < nkt; i += 2) {
-            FDC_ITER(g0, i);
-            FDC_ITER(g1, i + 1);
+        for (; i + 2 < nkt; i += 3) {          // tile t travels in set t % 3
+            FDC_ITER(g2, i);
+            FDC_ITER(g0, i + 1);
+            FDC_ITER(g1, i + 2);
+        }
+        if (i < nkt) {
+            FDC_ITER(g2, i);
+            ++i;
         }
         if (i < nkt) FDC_MMA(stg);
     }
