@@ -43,7 +43,7 @@ struct fdc_ctx {
     int Mp = kMaxRowsDense;              // rows the workspace is laid out for (multiple of 16)
 
     // attention launch shape for the largest step
-    int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1, attn_variant = 0;
+    int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1, attn_variant = 0, attn_wq = 4;
 
     // workspace
     char* ws = nullptr;
@@ -117,14 +117,18 @@ void plan_attention(fdc_ctx* c) {
     long want_wgs = (large ? 256L : 64L) * (c->m.head_dim == 128 ? 1 : 2);
     if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
     if (const char* e = std::getenv("FDC_ATTN_VARIANT")) c->attn_variant = std::atoi(e) == 1 ? 1 : 0;
-    const long masked_total = c->NB - c->P / 32;
-    long cb;
+    const long t0 = c->P / 32, masked_total = c->NB - t0;
+    long cb, total = c->NB;
     if (c->attn_variant == 1 && !std::getenv("FDC_ATTN_WGS")) {
-        // whole rounds of workgroups over the compute units: the cheapest of
-        // (rounds) x (tiles per chunk + a fixed set-up and merge cost)
+        // Tiles past the prefix carry masks and measure about 2.25 plain tiles
+        // each (table set-up included): chunks are cut equal in weighted tiles.
+        // Whole rounds of workgroups over the compute units: the cheapest of
+        // (rounds) x (weighted tiles per chunk + a fixed set-up and merge cost).
+        c->attn_wq = 9;
+        total = t0 + (masked_total * c->attn_wq + 3) / 4;
         long best = 0, best_cost = 0;
-        for (long ch = 1; ch <= std::max(1L, (long)c->NB / 8); ++ch) {
-            const long t = (c->NB + ch - 1) / ch;
+        for (long ch = 1; ch <= std::max(1L, total / 8); ++ch) {
+            const long t = (total + ch - 1) / ch;
             if (t > kMaxChunkTilesReg) continue;
             const long cost = ((zr * ch + 255) / 256) * (t + 6);
             if (best == 0 || cost < best_cost) {
@@ -132,7 +136,7 @@ void plan_attention(fdc_ctx* c) {
                 best_cost = cost;
             }
         }
-        cb = best ? (c->NB + best - 1) / best : kMaxChunkTilesReg;
+        cb = best ? (total + best - 1) / best : kMaxChunkTilesReg;
     } else {
         const long chunks = std::max(1L, (want_wgs + zr / 2) / zr);
         cb = (c->NB + chunks - 1) / chunks;
@@ -141,7 +145,7 @@ void plan_attention(fdc_ctx* c) {
     }
     if (masked_total > kMaxMaskedTiles) cb = std::min(cb, (long)kMaxMaskedTiles);
     c->attn_cb = (int)cb;
-    c->attn_chunks = (int)((c->NB + cb - 1) / cb);
+    c->attn_chunks = (int)((total + cb - 1) / cb);
 }
 
 size_t carve(fdc_ctx* c) {
@@ -255,6 +259,7 @@ void fill_attn(const fdc_ctx* c, int layer, int R, int T, AttnArgs* a) {
     a->P = c->P;
     a->NB = c->NB;
     a->CB = c->attn_cb;
+    a->wq = c->attn_wq;
     a->n_chunks = c->attn_chunks;
     a->nrt = c->attn_nrt;
     a->variant = c->attn_variant;

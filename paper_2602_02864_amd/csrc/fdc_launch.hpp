@@ -92,7 +92,8 @@ struct AttnArgs {
     float* out_f32;           // merge output: fp32 [M][Hq*D] ...
     uint16_t* out_hi;         // ... or fragments with K = Hq*D
     uint16_t* out_lo;
-    int Hq, Hkv, G, D, P, NB, CB, n_chunks, n_rg, nrt;
+    int Hq, Hkv, G, D, P, NB, CB, n_chunks, n_rg, nrt;   // CB: weighted tiles per chunk
+    int wq;                   // weight of a tile past the prefix, in quarters of a prefix tile
     int variant;              // 0: LDS-shared tiles (direct-to-LDS ring), 1: tiles in registers
     float scale_log2;         // log2(e) / sqrt(D)
 };
