@@ -39,7 +39,17 @@ namespace fdc {
 
 namespace {
 
-constexpr float kNegBig = -1.0e30f;
+constexpr float kNegBig = -1.0e30f;     // score of a masked key
+// The running maximum (log2 domain) never drops below this, so a masked score's
+// exponent stays hugely negative and its weight is exactly 0 without a second
+// masking pass, also for a row that has seen no visible key yet.
+constexpr float kMaxFloor = -1.0e20f;
+
+// score or kNegBig by visibility bit k of `bits`, without a compare
+__device__ __forceinline__ float keep_if(float x, uint32_t bits, int k) {
+    const uint32_t keep = (uint32_t)((int32_t)(bits << (31 - k)) >> 31);
+    return __uint_as_float((__float_as_uint(x) & keep) | (__float_as_uint(kNegBig) & ~keep));
+}
 constexpr int kStages = 4;
 constexpr int kStreams = 2;
 
@@ -247,7 +257,7 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     __builtin_amdgcn_s_waitcnt(0);
 
     f32x16 o[DT];
-    float m_run = kNegBig, l_run = 0.f;
+    float m_run = kMaxFloor, l_run = 0.f;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -314,7 +324,7 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
         float mx = kNegBig;
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            if (MASKED) sc[k] = (vbits >> k & 1u) ? sc[k] : kNegBig;
+            if (MASKED) sc[k] = keep_if(sc[k], vbits, k);
             mx = fmaxf(mx, sc[k]);
         }
         mx = fmaxf(mx, other_half(mx, hh));
@@ -326,7 +336,6 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             p[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[k], a.scale_log2, -m_new));
-            if (MASKED) p[k] = (vbits >> k & 1u) ? p[k] : 0.f;
             psum += p[k];
         }
         l_run = l_run * alpha + psum;
@@ -563,7 +572,7 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     float m_run[NRT], l_run[NRT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
-        m_run[rt] = kNegBig;
+        m_run[rt] = kMaxFloor;
         l_run[rt] = 0.f;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -619,7 +628,7 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
             float mx = kNegBig;
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                if (MASKED) sc[rt][k] = (vbits >> k & 1u) ? sc[rt][k] : kNegBig;
+                if (MASKED) sc[rt][k] = keep_if(sc[rt][k], vbits, k);
                 mx = fmaxf(mx, sc[rt][k]);
             }
             mx = fmaxf(mx, other_half(mx, hh));
@@ -631,7 +640,6 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
                 p[k] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[rt][k], a.scale_log2, -m_new));
-                if (MASKED) p[k] = (vbits >> k & 1u) ? p[k] : 0.f;
                 psum += p[k];
             }
             l_run[rt] = l_run[rt] * alpha + psum;
