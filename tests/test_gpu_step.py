@@ -85,7 +85,8 @@ def test_random_small_models_ragged_templates(seed, B, T, D):
 @pytest.mark.parametrize("seed,B,T,R,Hq,Hkv,D,F", [(4, 4, 2, 5, 4, 2, 64, 5),      # 40 rows
                                                    (5, 3, 4, 6, 14, 2, 64, 8),     # 72 rows, 168 per kv head
                                                    (6, 8, 4, 5, 8, 2, 128, 6),     # 160 rows: two row blocks
-                                                   (7, 2, 3, 3, 4, 4, 128, 4)])    # 18 rows: just above 16
+                                                   (7, 2, 3, 3, 4, 4, 128, 4),     # 18 rows: just above 16
+                                                   (8, 8, 4, 32, 8, 2, 64, 32)])   # up to 1024 rows: the row limit
 def test_many_rows_per_step_use_the_tiled_projections(seed, B, T, R, Hq, Hkv, D, F):
     """More than 16 rows in a step (several scenes, several tokens per branch:
     the multi-token masked prefill inside a slot): the projections switch to the
