@@ -25,8 +25,9 @@
  *  - rows of a step are ordered m = (scene * R + branch) * T + t.
  *  - limits: n_fields <= 64 for a context; head_dim in {64, 128};
  *    d_model, n_q_heads*head_dim and d_mlp multiples of 32, vocab of 4;
- *    d_model <= 5120; B*R*T <= 16 rows per step for the dense projections
- *    (FDC_ECAP otherwise).
+ *    d_model <= 5120; B*R*T <= 1024 rows per step (FDC_ECAP otherwise).  Up to
+ *    16 rows the projections stream the weights once (HBM-bound kernels), above
+ *    that they run as tiled matrix-core products.
  */
 #ifndef FDC_H
 #define FDC_H
