@@ -771,9 +771,12 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm
             ml[j] = pml[(size_t)c * NR];
             o[j] = po[(size_t)c * Q4];
         }
+        // all loads above are in flight together; entries past the last chunk
+        // (repeats of it) get weight 0 instead of a branch, which would push the
+        // arrays out of registers and serialise the loads
 #pragma unroll
         for (int j = 0; j < CB; ++j) {
-            if (c0 + j >= a.n_chunks) break;
+            if (c0 + j >= a.n_chunks) ml[j] = make_float2(kNegBig, 0.f);
             const float mn = fmaxf(mg, ml[j].x);
             const float e_old = __builtin_amdgcn_exp2f(mg - mn), e_new = __builtin_amdgcn_exp2f(ml[j].x - mn);
             L = L * e_old + ml[j].y * e_new;
