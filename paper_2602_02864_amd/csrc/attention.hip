@@ -134,6 +134,77 @@ __device__ __forceinline__ float other_half(float x, int hh) {
 
 // QF32: the queries come in fp32 (inside the decode step) and are used as bf16
 // head + tail; otherwise they are bf16 data and have no tail.
+// Start-up tables of a workgroup: its rows, and for the tiles of its chunk that
+// reach past the prefix one 32-key visibility word per (tile, row) plus their
+// OR per tile.  Everything read from memory (branch tables, slot starts, valid
+// lengths, ancestor words) is fetched in one round trip; the words are computed
+// once per branch row (the G query heads of a branch token share them) and then
+// copied to the rows.  Ends with a barrier.
+template <int NR, int NT>
+__device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& sm, int b, int kvh, int rg, int mt0,
+                                             int nmt, int* row_m, int* row_head, int* row_field, int* row_off,
+                                             int* s_start, int* vlen, unsigned long long* anc_l,
+                                             uint32_t (*bmask)[NR], uint32_t (*rowmask)[NR], uint32_t* tile_any) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int F = sm.F;
+    for (int r = tid; r < NR; r += NT) {
+        const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
+        row_m[r] = ri.m;
+        row_head[r] = ri.head;
+        row_field[r] = ri.field;
+        row_off[r] = ri.off;
+    }
+    if (nmt > 0)                                      // uniform: the chunk reaches into the slots
+        for (int g = tid; g < F; g += NT) {
+            s_start[g] = sm.slot_start[g];
+            vlen[g] = sm.valid_len[b * F + g];
+            anc_l[g] = a.anc[g];
+        }
+    __syncthreads();
+    if (nmt > 0) {
+        // branch rows of this row group: jr = (rg * NR + r) / G
+        const int jr0 = (rg * NR) / a.G, nbr = (rg * NR + NR - 1) / a.G - jr0 + 1;
+        for (int idx = tid; idx < nmt * nbr; idx += NT) {
+            const int t = idx / nbr, j = idx % nbr;
+            const int r = max(0, (jr0 + j) * a.G - rg * NR);      // a row of that branch row
+            const int key0 = (mt0 + t) * 32;
+            const int f = row_field[r];
+            uint32_t bits = 0;
+            if (row_m[r] >= 0) {
+                if (key0 < a.P) {
+                    const int nb = min(a.P - key0, 32);
+                    bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
+                }
+                const unsigned long long anc = anc_l[f];
+                for (int g = 0; g < F; ++g) {
+                    const int s0 = s_start[g];
+                    if (s0 >= key0 + 32) break;        // slots are laid out in field order
+                    // keys of slot g this row sees: its own up to its token, an ancestor's all written
+                    const int n = g == f ? row_off[r] + 1 : ((anc >> g) & 1ull) ? vlen[g] : 0;
+                    const int lo = max(s0, key0), hi = min(s0 + n, key0 + 32);
+                    if (hi > lo) {
+                        const int nb = hi - lo;
+                        bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
+                    }
+                }
+            }
+            bmask[t][j] = bits;
+        }
+        __syncthreads();
+        for (int idx = tid; idx < nmt * NR; idx += NT) {
+            const int t = idx / NR, r = idx % NR;
+            rowmask[t][r] = row_m[r] >= 0 ? bmask[t][(rg * NR + r) / a.G - jr0] : 0u;
+        }
+        __syncthreads();
+        for (int t = wave; t < nmt; t += NT / 64) {
+            uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
+            for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
+            if (lane == 0) tile_any[t] = v;
+        }
+    }
+    __syncthreads();
+}
+
 template <int D, int NRT, bool QF32>
 __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnArgs a, StepMeta sm) {
     constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, NT = kStreams * NRT * 64;
@@ -141,11 +212,12 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     constexpr int LPT = 2 * DJ;                     // 1 KiB load instructions per K+V tile
     constexpr int LPW = LPT / NRT;                  // ... issued by each wavefront of a stream
     __shared__ __attribute__((aligned(16))) uint16_t stage[kStreams][kStages][2 * TILE];
-    __shared__ uint16_t vis[NR][kMaxFields + 2];
+    __shared__ uint32_t bmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t tile_any[kMaxMaskedTiles];
     __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
-    __shared__ int s_start[kMaxFields];
+    __shared__ int s_start[kMaxFields], vlen[kMaxFields];
+    __shared__ unsigned long long anc_l[kMaxFields];
     __shared__ uint16_t act_list[kStreams][kMaxChunkTiles / kStreams];
     __shared__ int n_act[kStreams];
     __shared__ float xm[NR], xl[NR];
@@ -161,56 +233,8 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     const int nmt = max(0, blk_end - mt0);
 
     // ---- start-up: rows, per-slot visible counts, visibility words, tile lists ---
-    for (int r = tid; r < NR; r += NT) {
-        const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
-        row_m[r] = ri.m;
-        row_head[r] = ri.head;
-        row_field[r] = ri.field;
-        row_off[r] = ri.off;
-    }
-    if (nmt > 0) {                                   // uniform: the chunk reaches into the slots
-        for (int g = tid; g < F; g += NT) s_start[g] = sm.slot_start[g];
-        __syncthreads();
-        for (int idx = tid; idx < NR * F; idx += NT) {
-            const int r = idx / F, g = idx % F;
-            const int f = row_field[r];
-            int n = 0;
-            if (f >= 0) {
-                if (g == f) n = row_off[r] + 1;
-                else if ((a.anc[f] >> g) & 1ull) n = sm.valid_len[b * F + g];
-            }
-            vis[r][g] = (uint16_t)n;
-        }
-        __syncthreads();
-        for (int idx = tid; idx < nmt * NR; idx += NT) {
-            const int t = idx / NR, r = idx % NR;
-            const int key0 = (mt0 + t) * 32;
-            uint32_t bits = 0;
-            if (row_m[r] >= 0) {
-                if (key0 < a.P) {
-                    const int nb = min(a.P - key0, 32);
-                    bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                }
-                for (int g = 0; g < F; ++g) {
-                    const int s0 = s_start[g];
-                    if (s0 >= key0 + 32) break;        // slots are laid out in field order
-                    const int lo = max(s0, key0), hi = min(s0 + (int)vis[r][g], key0 + 32);
-                    if (hi > lo) {
-                        const int nb = hi - lo;
-                        bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
-                    }
-                }
-            }
-            rowmask[t][r] = bits;
-        }
-        __syncthreads();
-        for (int t = wave; t < nmt; t += NT / 64) {
-            uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
-            for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
-            if (lane == 0) tile_any[t] = v;
-        }
-    }
-    __syncthreads();
+    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, s_start, vlen, anc_l,
+                         bmask, rowmask, tile_any);
     if (wave < kStreams) {
         // candidates of stream w: tiles cb0 + w, cb0 + w + 2, ...; keep the visible ones
         const int blk = cb0 + wave + kStreams * lane;
@@ -450,11 +474,12 @@ template <int D, int NRT, bool QF32>
 __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepMeta sm) {
     constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, NT = 256;
     constexpr int TILE = 32 * D;
-    __shared__ uint16_t vis[NR][kMaxFields + 2];
+    __shared__ uint32_t bmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t tile_any[kMaxMaskedTiles];
     __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
-    __shared__ int s_start[kMaxFields];
+    __shared__ int s_start[kMaxFields], vlen[kMaxFields];
+    __shared__ unsigned long long anc_l[kMaxFields];
     __shared__ uint16_t act_list[kMaxChunkTilesReg];
     __shared__ int n_act_sh;
     __shared__ float red_m[4][NR], red_l[4][NR];
@@ -476,56 +501,8 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     const int mt0 = max(cb0, a.P >> 5);
     const int nmt = max(0, blk_end - mt0);
 
-    for (int r = tid; r < NR; r += NT) {
-        const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
-        row_m[r] = ri.m;
-        row_head[r] = ri.head;
-        row_field[r] = ri.field;
-        row_off[r] = ri.off;
-    }
-    if (nmt > 0) {
-        for (int g = tid; g < F; g += NT) s_start[g] = sm.slot_start[g];
-        __syncthreads();
-        for (int idx = tid; idx < NR * F; idx += NT) {
-            const int r = idx / F, g = idx % F;
-            const int f = row_field[r];
-            int n = 0;
-            if (f >= 0) {
-                if (g == f) n = row_off[r] + 1;
-                else if ((a.anc[f] >> g) & 1ull) n = sm.valid_len[b * F + g];
-            }
-            vis[r][g] = (uint16_t)n;
-        }
-        __syncthreads();
-        for (int idx = tid; idx < nmt * NR; idx += NT) {
-            const int t = idx / NR, r = idx % NR;
-            const int key0 = (mt0 + t) * 32;
-            uint32_t bits = 0;
-            if (row_m[r] >= 0) {
-                if (key0 < a.P) {
-                    const int nb = min(a.P - key0, 32);
-                    bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                }
-                for (int g = 0; g < F; ++g) {
-                    const int s0 = s_start[g];
-                    if (s0 >= key0 + 32) break;
-                    const int lo = max(s0, key0), hi = min(s0 + (int)vis[r][g], key0 + 32);
-                    if (hi > lo) {
-                        const int nb = hi - lo;
-                        bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
-                    }
-                }
-            }
-            rowmask[t][r] = bits;
-        }
-        __syncthreads();
-        for (int t = wave; t < nmt; t += 4) {
-            uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
-            for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
-            if (lane == 0) tile_any[t] = v;
-        }
-    }
-    __syncthreads();
+    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, s_start, vlen, anc_l,
+                         bmask, rowmask, tile_any);
     if (wave == 0) {
         int base = 0;
         for (int c0 = 0; c0 < a.CB; c0 += 64) {               // CB <= kMaxChunkTilesReg
