@@ -154,12 +154,14 @@ __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& 
         row_field[r] = ri.field;
         row_off[r] = ri.off;
     }
-    if (nmt > 0)                                      // uniform: the chunk reaches into the slots
+    if (nmt > 0) {                                    // uniform: the chunk reaches into the slots
         for (int g = tid; g < F; g += NT) {
             s_start[g] = sm.slot_start[g];
             vlen[g] = sm.valid_len[b * F + g];
             anc_l[g] = a.anc[g];
         }
+        for (int t = tid; t < nmt; t += NT) tile_any[t] = 0u;
+    }
     __syncthreads();
     if (nmt > 0) {
         // branch rows of this row group: jr = (rg * NR + r) / G
@@ -176,9 +178,10 @@ __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& 
                     bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
                 }
                 const unsigned long long anc = anc_l[f];
-                for (int g = 0; g < F; ++g) {
+                for (int g = 0; g < F; ++g) {            // slots are laid out in field order
+                    if (g + 1 < F && s_start[g + 1] <= key0) continue;     // ends before the tile
                     const int s0 = s_start[g];
-                    if (s0 >= key0 + 32) break;        // slots are laid out in field order
+                    if (s0 >= key0 + 32) break;
                     // keys of slot g this row sees: its own up to its token, an ancestor's all written
                     const int n = g == f ? row_off[r] + 1 : ((anc >> g) & 1ull) ? vlen[g] : 0;
                     const int lo = max(s0, key0), hi = min(s0 + n, key0 + 32);
@@ -187,6 +190,7 @@ __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& 
                         bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
                     }
                 }
+                if (bits) atomicOr(&tile_any[t], bits);
             }
             bmask[t][j] = bits;
         }
@@ -194,12 +198,6 @@ __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& 
         for (int idx = tid; idx < nmt * NR; idx += NT) {
             const int t = idx / NR, r = idx % NR;
             rowmask[t][r] = row_m[r] >= 0 ? bmask[t][(rg * NR + r) / a.G - jr0] : 0u;
-        }
-        __syncthreads();
-        for (int t = wave; t < nmt; t += NT / 64) {
-            uint32_t v = lane < NR ? rowmask[t][lane] : 0u;
-            for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o);
-            if (lane == 0) tile_any[t] = v;
         }
     }
     __syncthreads();
@@ -483,7 +481,7 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     __shared__ uint16_t act_list[kMaxChunkTilesReg];
     __shared__ int n_act_sh;
     __shared__ float red_m[4][NR], red_l[4][NR];
-    __shared__ f32x4 red_o[NRT * DT * 4 * 64];
+    __shared__ f32x4 red_o[2 * NRT * DT * 4 * 64];
     __shared__ bf16x8 qlo[QF32 ? NRT * DJ * 64 : 1];
 
     // Row groups of the same (scene, KV head, chunk) read the same tiles: they
@@ -681,8 +679,13 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
 #pragma unroll
             for (int k = 0; k < 16; ++k) o[rt][dt][k] *= e;
     }
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    // two rounds instead of four: wavefronts 0 and 1 store into a buffer each,
+    // wavefronts 2 and 3 add into them, the store to memory adds the two:
+    // (w0 + w2) + (w1 + w3), the same order every time
+    constexpr int Q = NRT * DT * 4 * 64;
+    for (int round = 0; round < 2; ++round) {
+        if ((wave >> 1) == round) {
+            f32x4* dst = red_o + (wave & 1) * Q;
 #pragma unroll
             for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
@@ -692,15 +695,15 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
                         const f32x4 v = {o[rt][dt][4 * i4], o[rt][dt][4 * i4 + 1], o[rt][dt][4 * i4 + 2],
                                          o[rt][dt][4 * i4 + 3]};
                         const int idx = ((rt * DT + dt) * 4 + i4) * 64 + lane;
-                        if (w == 0) red_o[idx] = v;
-                        else red_o[idx] += v;
+                        if (round == 0) dst[idx] = v;
+                        else dst[idx] += v;
                     }
         }
         __syncthreads();
     }
     const size_t pidx = ((size_t)z * a.n_rg + rg) * a.n_chunks + chunk;
-    f32x4* po = reinterpret_cast<f32x4*>(a.part_o) + pidx * (NRT * DT * 4 * 64);
-    for (int q = tid; q < NRT * DT * 4 * 64; q += 256) po[q] = red_o[q];
+    f32x4* po = reinterpret_cast<f32x4*>(a.part_o) + pidx * Q;
+    for (int q = tid; q < Q; q += 256) po[q] = red_o[q] + red_o[Q + q];
     if (tid < NR) {
         float* ml = a.part_ml + (pidx * NR + tid) * 2;
         ml[0] = fmaxf(fmaxf(red_m[0][tid], red_m[1][tid]), fmaxf(red_m[2][tid], red_m[3][tid]));
