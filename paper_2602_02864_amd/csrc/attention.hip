@@ -54,7 +54,7 @@ constexpr int kStages = 4;
 constexpr int kStreams = 2;
 
 // First tile of chunk c.  Tiles that reach past the prefix carry masks and cost
-// more (measured: about 2.25 plain tiles each, their table set-up included), so
+// more (measured: about 1.5 plain tiles each, their table set-up included), so
 // chunks are equal in weighted tiles: a tile past the prefix counts wq / 4.
 __device__ __forceinline__ int chunk_start(const AttnArgs& a, int c) {
     const int t0 = a.P >> 5;

@@ -120,11 +120,11 @@ void plan_attention(fdc_ctx* c) {
     const long t0 = c->P / 32, masked_total = c->NB - t0;
     long cb, total = c->NB;
     if (c->attn_variant == 1 && !std::getenv("FDC_ATTN_WGS")) {
-        // Tiles past the prefix carry masks and measure about 2.25 plain tiles
+        // Tiles past the prefix carry masks and measure about 1.5 plain tiles
         // each (table set-up included): chunks are cut equal in weighted tiles.
         // Whole rounds of workgroups over the compute units: the cheapest of
         // (rounds) x (weighted tiles per chunk + a fixed set-up and merge cost).
-        c->attn_wq = 9;
+        c->attn_wq = 6;
         total = t0 + (masked_total * c->attn_wq + 3) / 4;
         long best = 0, best_cost = 0;
         for (long ch = 1; ch <= std::max(1L, total / 8); ++ch) {
