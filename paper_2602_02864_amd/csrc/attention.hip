@@ -513,33 +513,9 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
         }
         if (lane == 0) n_act_sh = base;
     }
-    // query operand: head (bf16) in registers, tail in LDS
+    // query operand: head (bf16) in registers, tail in LDS (filled below, after the
+    // first tile is on its way)
     Frag qh[NRT][DJ];
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-        const int r = rt * 32 + r32;
-        const int m = row_m[r];
-#pragma unroll
-        for (int j = 0; j < DJ; ++j) {
-            Frag lo;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) qh[rt][j].u[k] = lo.u[k] = 0;
-            if (m >= 0) {
-                const size_t qo = ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh;
-                if (QF32) {
-                    const f32x4 q0 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo);
-                    const f32x4 q1 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 4);
-                    split2(q0[0], q0[1], qh[rt][j].u[0], lo.u[0]);
-                    split2(q0[2], q0[3], qh[rt][j].u[1], lo.u[1]);
-                    split2(q1[0], q1[1], qh[rt][j].u[2], lo.u[2]);
-                    split2(q1[2], q1[3], qh[rt][j].u[3], lo.u[3]);
-                } else {
-                    qh[rt][j].v = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo);
-                }
-            }
-            if (QF32 && wave == 0) qlo[(rt * DJ + j) * 64 + lane] = lo.v;
-        }
-    }
     __syncthreads();
     const int n_act = n_act_sh;
 
@@ -642,6 +618,32 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     Frag kn[DJ], vn[DT][2];
     int i = wave;
     if (i < n_act) load_tile(act_list[i], kn, vn);
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+        const int r = rt * 32 + r32;
+        const int m = row_m[r];
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) {
+            Frag lo;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) qh[rt][j].u[k] = lo.u[k] = 0;
+            if (m >= 0) {
+                const size_t qo = ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh;
+                if (QF32) {
+                    const f32x4 q0 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo);
+                    const f32x4 q1 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 4);
+                    split2(q0[0], q0[1], qh[rt][j].u[0], lo.u[0]);
+                    split2(q0[2], q0[3], qh[rt][j].u[1], lo.u[1]);
+                    split2(q1[0], q1[1], qh[rt][j].u[2], lo.u[2]);
+                    split2(q1[2], q1[3], qh[rt][j].u[3], lo.u[3]);
+                } else {
+                    qh[rt][j].v = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo);
+                }
+            }
+            if (QF32 && wave == 0) qlo[(rt * DJ + j) * 64 + lane] = lo.v;
+        }
+    }
+    if (QF32) __syncthreads();                       // the query tails are in LDS
     while (i < n_act) {
         // keeps the query tail in LDS (re-read per tile) instead of in registers
         if (QF32) asm volatile("" ::: "memory");
