@@ -77,6 +77,13 @@ __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm)
                     for (int i = 0; i < VEC; ++i) v[i] += p[j][i];
         }
     }
+    // the gains are requested before the reduction, not after it
+    f32x4 gain[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        const int q = threadIdx.x + i * NT;
+        gain[i] = q < nvec ? *reinterpret_cast<const f32x4*>(a.gain + 4 * q) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
@@ -90,8 +97,7 @@ __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm)
         const int k = 4 * q;
         *reinterpret_cast<f32x4*>(a.x + (size_t)m * a.d + k) = v[i];
         if (a.hidden_x) *reinterpret_cast<f32x4*>(a.hidden_x + (size_t)m * a.d + k) = v[i];
-        const f32x4 g = *reinterpret_cast<const f32x4*>(a.gain + k);
-        const f32x4 n = v[i] * rstd * g;
+        const f32x4 n = v[i] * rstd * gain[i];
         uint16_t hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) split_bf16(n[j], hi[j], lo[j]);
