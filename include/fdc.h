@@ -113,22 +113,38 @@ int32_t fdc_dense_mask(int32_t n_fields, const int32_t* slot_len, const int32_t*
                        uint8_t* mask, int32_t* pos);
 
 /* ---------------------------------------------------------------------------
- * Algorithm 1 (host only): in-degree counters and the ready set.  A field is
- * "finished" after content_len[f] decoded tokens (the caller's stand-in for
- * "the model ended the line"; at most the slot length).  Each fdc_sched_next
- * returns the ready fields in field order with their next slot offset, pads the
- * arrays [max_branches] with field -1, and then accounts one decoded token per
- * ready field: finished fields leave the set and release successors whose last
- * prerequisite they were.  *n_active == 0 means every field is complete.  The
- * number of non-empty passes equals the critical-path length of the template.
+ * Algorithm 1 (host only): in-degree counters and the ready set.
+ *
+ * fdc_sched_peek returns the ready fields in field order with their next slot
+ * offset and pads the arrays [max_branches] with field -1; *n_active == 0 means
+ * every field is complete.  fdc_sched_advance then accounts one decoded token
+ * per ready field; field_finished[i] != 0 says that the i-th field peek
+ * returned is finished (the model ended its line, or its slot is full): it
+ * leaves the set and releases the successors whose last prerequisite it was.
+ * fdc_sched_complete marks a field whose tokens are known beforehand (fixed
+ * template text, Sec. 3.3) as finished with n_tokens tokens without a pass; its
+ * prerequisites must be complete already.
+ *
+ * fdc_sched_next is peek + advance with "finished" := content_len[f] tokens
+ * decoded (the caller's stand-in for the model ending the line; needs a
+ * scheduler created with content_len != NULL, each >= 1).  With it the number
+ * of non-empty passes equals the critical-path length of the template.
+ * fdc_sched_stats: passes and tokens accounted so far, fields not finished yet
+ * (each pointer may be NULL).
  * Errors: as fdc_build_mask for the graph; FDC_ECAP if more than max_branches
- * fields are ready.
+ * fields are ready; FDC_EINVAL if n differs from the size of the ready set.
  */
 typedef struct fdc_sched fdc_sched;
 int32_t fdc_sched_create(int32_t n_fields, int32_t n_edges, const int32_t* edge_src,
-                         const int32_t* edge_dst, const int32_t* content_len, fdc_sched** out);
+                         const int32_t* edge_dst, const int32_t* content_len /* or NULL */,
+                         fdc_sched** out);
+int32_t fdc_sched_peek(fdc_sched* s, int32_t max_branches, int32_t* branch_field,
+                       int32_t* branch_off, int32_t* n_active);
+int32_t fdc_sched_advance(fdc_sched* s, int32_t n, const int32_t* field_finished);
+int32_t fdc_sched_complete(fdc_sched* s, int32_t field, int32_t n_tokens);
 int32_t fdc_sched_next(fdc_sched* s, int32_t max_branches, int32_t* branch_field,
                        int32_t* branch_off, int32_t* n_active);
+int32_t fdc_sched_stats(const fdc_sched* s, int64_t* passes, int64_t* tokens, int32_t* n_unfinished);
 void    fdc_sched_destroy(fdc_sched* s);
 
 /* ---------------------------------------------------------------------------
@@ -221,6 +237,47 @@ int32_t fdc_parallel_decode_step(fdc_ctx* ctx, int32_t n_branches, int32_t T,
                                  const int32_t* tok_in, const void* emb_in,
                                  int32_t* tok_out, float* gap_out,
                                  float* logits_out, float* hidden_out, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Algorithm 1 end to end (Sec. 3.2), with the finishing rules of Sec. 3.3: the
+ * template of every scene is decoded greedily from empty slots until every
+ * field is finished.  Each iteration runs one fdc_parallel_decode_step for the
+ * union of the scenes' ready sets (scenes whose sets differ share the pass;
+ * R = the largest set), reads the produced tokens back and decides on the host
+ * which fields are finished: a field is finished when the token it just
+ * produced is one of eos_ids (the model ended the line) or when its slot is
+ * full (truncation to the fixed length).  A field's first input is
+ * start_token[f] at slot offset 0; afterwards its previous output.  The
+ * finishing token is recorded but not fed back, so valid_len[f] afterwards is
+ * the number of tokens recorded for f.
+ *
+ * Fixed template text (field names; "pre-filled, visible to all subsequent
+ * tokens"): a field with fixed_len[f] > 0 holds known tokens.  Such fields are
+ * written first, in field order, by multi-token passes of up to max_tokens
+ * tokens for all scenes at once, and count as finished from the start; the
+ * template's edges say who sees them (a header that every later field depends
+ * on is visible to all of them).  Every prerequisite of a fixed field must be
+ * fixed too.
+ *
+ *  start_token  host [F]     ignored for fixed fields
+ *  fixed_len    host [F] or NULL (no fixed fields)
+ *  fixed_tok    host, the fixed fields' tokens one after the other in field order
+ *  eos_ids      host [n_eos] (n_eos may be 0: every field runs to its slot length)
+ *  max_passes   > 0: FDC_ECAP if Algorithm 1 needs more passes; <= 0: no limit
+ *               (truncation bounds the loop by the longest chain of slots)
+ *  out_tok      host [B][F][Smax], Smax = the longest slot: recorded tokens
+ *               (for fixed fields their own tokens), -1 beyond out_len
+ *  out_len      host [B][F]
+ *  out_passes   host [2] or NULL: passes of Algorithm 1, passes spent on fixed fields
+ * Needs what fdc_parallel_decode_step needs, with the prefix K/V in the cache.
+ * Synchronises `stream` once per pass.  Errors: those of the step and of the
+ * scheduler (FDC_ECAP when a ready set exceeds max_branches); after an error
+ * the slots hold what was decoded so far.
+ */
+int32_t fdc_cot_decode(fdc_ctx* ctx, const int32_t* start_token, const int32_t* fixed_len,
+                       const int32_t* fixed_tok, const int32_t* eos_ids, int32_t n_eos,
+                       int32_t max_passes, int32_t* out_tok, int32_t* out_len, int32_t* out_passes,
+                       void* stream);
 
 /* The step's attention alone (Sec. 3.3 mask; "shared KV cache accessed by
  * multiple query tokens within a single attention kernel"): DAG-masked GQA

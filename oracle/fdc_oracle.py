@@ -444,3 +444,69 @@ def run_cot(dec, content_len, start_token, forced_tokens=None):
             last_tok[f] = int(out["tok"][i])
         trace.append({"branch_field": bf, "branch_off": bo, "tok_in": ti, "out": out})
     return trace
+
+
+def run_cot_dynamic(dec, start_token, eos_ids=(), fixed=None):
+    """Algorithm 1 with the finishing rules of Sec. 3.3, for every scene of `dec`.
+
+    A field is finished when the token it just produced is in `eos_ids` (the
+    model ended the line) or when its slot is full (truncation to the fixed
+    length).  The first input of a field is its start token; afterwards the
+    token it produced in the previous pass.  `fixed` maps a field to tokens
+    known from the start (template text): those fields are written before the
+    loop starts and count as finished; who sees them follows from the edges.
+    Scenes run Algorithm 1 independently and share each forward pass.
+
+    Returns text[b][v] (tokens recorded for field v of scene b), the number of
+    passes of the loop, and per pass what was decoded and the top-2 logit gaps.
+    """
+    F, B = len(dec.slot_len), dec.B
+    eos = set(int(t) for t in eos_ids)
+    fixed = {int(f): [int(t) for t in toks] for f, toks in (fixed or {}).items()}
+    preds = [set() for _ in range(F)]
+    succ = [set() for _ in range(F)]
+    for (u, v) in set(dec.edges):
+        preds[v].add(u)
+        succ[u].add(v)
+    dec.valid_len[:] = 0
+    text = [[[] for _ in range(F)] for _ in range(B)]
+    for f in sorted(fixed):
+        toks = fixed[f]
+        if not preds[f] <= set(fixed):
+            raise ValueError("a fixed field may only depend on fixed fields")
+        if not 0 < len(toks) <= dec.slot_len[f]:
+            raise ValueError("fixed text does not fit its slot")
+        dec.step([[f]] * B, [[0]] * B, tok_in=np.array([toks] * B, dtype=np.int32).reshape(B, 1, len(toks)),
+                 T=len(toks))
+        for b in range(B):
+            text[b][f] = list(toks)
+    # d_v and S of Algorithm 1, one copy per scene; fixed fields have signalled already
+    d = [[len(preds[v] - set(fixed)) for v in range(F)] for _ in range(B)]
+    S = [{v for v in range(F) if d[b][v] == 0 and v not in fixed} for b in range(B)]
+    last = [list(start_token) for _ in range(B)]
+    trace = []
+    while any(S):
+        R = max(len(s) for s in S)
+        bf = np.full((B, R), -1, dtype=np.int32)
+        bo = np.zeros((B, R), dtype=np.int32)
+        ti = np.zeros((B, R, 1), dtype=np.int32)
+        for b in range(B):
+            for i, v in enumerate(sorted(S[b])):
+                bf[b, i], bo[b, i], ti[b, i, 0] = v, len(text[b][v]), last[b][v]
+        out = dec.step(bf, bo, tok_in=ti)
+        gaps = []
+        for b in range(B):
+            for i, v in enumerate(sorted(S[b])):
+                t = int(out["tok"][b * R + i])
+                gaps.append(float(out["gap"][b * R + i]))
+                text[b][v].append(t)
+                last[b][v] = t
+                if t in eos or len(text[b][v]) >= dec.slot_len[v]:
+                    S[b].discard(v)
+                    for u in succ[v]:
+                        d[b][u] -= 1
+                        if d[b][u] == 0:
+                            S[b].add(u)
+        trace.append({"branch_field": bf, "branch_off": bo, "tok_in": ti, "gaps": gaps})
+    return {"text": text, "passes": len(trace), "trace": trace,
+            "min_gap": min((g for p in trace for g in p["gaps"]), default=float("inf"))}

@@ -32,6 +32,8 @@ EXPORTS = [
     "fdc_profile_enable", "fdc_profile_read", "fdc_profile_kind_name",
     "fdc_profile_calibrate", "fdc_stream_copy",
     "fdc_sched_create", "fdc_sched_next", "fdc_sched_destroy",
+    "fdc_sched_peek", "fdc_sched_advance", "fdc_sched_complete", "fdc_sched_stats",
+    "fdc_cot_decode",
 ]
 FDC_PROF_KINDS = 9
 
@@ -132,6 +134,16 @@ def lib() -> C.CDLL:
     L.fdc_sched_next.argtypes = [vp, i32, pi32, pi32, pi32]
     L.fdc_sched_destroy.restype = None
     L.fdc_sched_destroy.argtypes = [vp]
+    L.fdc_sched_peek.restype = i32
+    L.fdc_sched_peek.argtypes = [vp, i32, pi32, pi32, pi32]
+    L.fdc_sched_advance.restype = i32
+    L.fdc_sched_advance.argtypes = [vp, i32, pi32]
+    L.fdc_sched_complete.restype = i32
+    L.fdc_sched_complete.argtypes = [vp, i32, i32]
+    L.fdc_sched_stats.restype = i32
+    L.fdc_sched_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(i32)]
+    L.fdc_cot_decode.restype = i32
+    L.fdc_cot_decode.argtypes = [vp, pi32, pi32, pi32, pi32, i32, i32, pi32, pi32, pi32, vp]
     _lib = L
     return L
 
@@ -207,6 +219,45 @@ def fdc_schedule(n_fields: int, edges, content_len, max_branches: Optional[int] 
     finally:
         lib().fdc_sched_destroy(h)
     return passes
+
+
+class Scheduler:
+    """fdc_sched_* with finishing decided by the caller (peek / advance / complete)."""
+
+    def __init__(self, n_fields: int, edges, content_len=None):
+        src, dst = _edges(edges)
+        self.F = n_fields
+        self._h = C.c_void_p()
+        cl = _i32(content_len) if content_len is not None else None
+        _check(lib().fdc_sched_create(n_fields, src.size, _p(src), _p(dst),
+                                      _p(cl) if cl is not None else None, C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().fdc_sched_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+    def peek(self, max_branches: Optional[int] = None):
+        R = max_branches or self.F
+        bf = np.zeros(R, dtype=np.int32)
+        bo = np.zeros(R, dtype=np.int32)
+        n = C.c_int32(0)
+        _check(lib().fdc_sched_peek(self._h, R, _p(bf), _p(bo), C.byref(n)))
+        return bf[:n.value].copy(), bo[:n.value].copy()
+
+    def advance(self, finished):
+        fin = _i32(finished)
+        _check(lib().fdc_sched_advance(self._h, fin.size, _p(fin) if fin.size else None))
+
+    def complete(self, field: int, n_tokens: int):
+        _check(lib().fdc_sched_complete(self._h, field, n_tokens))
+
+    def stats(self):
+        p, t, u = C.c_int64(0), C.c_int64(0), C.c_int32(0)
+        _check(lib().fdc_sched_stats(self._h, C.byref(p), C.byref(t), C.byref(u)))
+        return {"passes": p.value, "tokens": t.value, "unfinished": u.value}
 
 
 # --------------------------------------------------------------------------- device
@@ -463,6 +514,29 @@ class Context:
             ptr("tok"), ptr("gap"), ptr("logits"), ptr("hidden"), _stream()))
         out["_inputs"] = (tok_t, emb_t)            # keep alive until the caller syncs
         return out
+
+    def cot_decode(self, start_token, eos_ids=(), fixed=None, max_passes: int = 0):
+        """fdc_cot_decode.  fixed: {field: token list} of pre-filled fields.  Returns
+        {"tok": [B][F][Smax], "len": [B][F], "passes", "fixed_passes"} (numpy, host)."""
+        F, B = len(self.slot_len), self.B
+        st = _i32(start_token)
+        if st.size != F:
+            raise ValueError("start_token needs one entry per field")
+        fl = np.zeros(F, dtype=np.int32)
+        ft = []
+        for f in sorted(fixed or {}):
+            fl[f] = len(fixed[f])
+            ft.extend(int(t) for t in fixed[f])
+        ft = _i32(ft)
+        eos = _i32(list(eos_ids))
+        Smax = int(max(self.slot_len))
+        tok = np.empty((B, F, Smax), dtype=np.int32)
+        ln = np.empty((B, F), dtype=np.int32)
+        ps = np.zeros(2, dtype=np.int32)
+        _check(lib().fdc_cot_decode(self._h, _p(st), _p(fl) if fixed else None, _p(ft) if ft.size else None,
+                                    _p(eos) if eos.size else None, eos.size, max_passes,
+                                    _p(tok), _p(ln), _p(ps), _stream()))
+        return {"tok": tok, "len": ln, "passes": int(ps[0]), "fixed_passes": int(ps[1])}
 
     def masked_attention(self, layer: int, q, branch_field, branch_off, T: int = 1):
         torch = self.torch

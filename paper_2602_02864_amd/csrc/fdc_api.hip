@@ -30,6 +30,7 @@ struct fdc_ctx {
     int F = 0, P = 0, N = 0, Npad = 0, NB = 0, B = 0, Rmax = 0, Tmax = 0, Mmax = 0;
     std::vector<int32_t> slot_len, slot_start, level, valid_len;
     std::vector<uint64_t> anc;
+    std::vector<int32_t> edge_src, edge_dst;
     std::vector<fdc_layer_weights> lw;
     std::vector<char> lw_set;
     const uint16_t* emb = nullptr;
@@ -59,6 +60,7 @@ struct fdc_ctx {
     hipEvent_t stage_ev[kStageSlots] = {};
     bool stage_used[kStageSlots] = {};
     int stage_next = 0;
+    int32_t* drv_host = nullptr;         // pinned: token inputs [Mmax], token outputs [Mmax] of the CoT driver
 
     // optional per-kernel timing with HIP events (benchmarks only)
     bool prof_on = false;
@@ -194,7 +196,7 @@ size_t carve(fdc_ctx* c) {
     const size_t NR = (size_t)c->attn_nrt * 32;
     c->off.attn_o = take(sizeof(float) * zr * c->attn_chunks * NR * m.head_dim);
     c->off.attn_ml = take(sizeof(float) * zr * c->attn_chunks * NR * 2);
-    c->off.tok_tmp = take(sizeof(int32_t) * c->Mmax);
+    c->off.tok_tmp = take(sizeof(int32_t) * 2 * c->Mmax);   // the CoT driver's token inputs, outputs
     c->off.end = o;
     return o;
 }
@@ -404,6 +406,10 @@ int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t*
         return rc;
     }
     c->slot_len.assign(slot_len, slot_len + n_fields);
+    if (n_edges > 0) {
+        c->edge_src.assign(edge_src, edge_src + n_edges);
+        c->edge_dst.assign(edge_dst, edge_dst + n_edges);
+    }
     c->P = prefix_len;
     c->N = N;
     c->Npad = (N + 31) / 32 * 32;
@@ -447,12 +453,18 @@ int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t*
             return fail(FDC_EHIP, "could not allocate pinned staging memory");
         }
     }
+    if (hipHostMalloc((void**)&c->drv_host, sizeof(int32_t) * 2 * c->Mmax, hipHostMallocDefault) != hipSuccess) {
+        c->drv_host = nullptr;
+        fdc_destroy(c);
+        return fail(FDC_EHIP, "could not allocate pinned staging memory");
+    }
     *out = c;
     return FDC_OK;
 }
 
 void fdc_destroy(fdc_ctx* c) {
     if (!c) return;
+    if (c->drv_host) (void)hipHostFree(c->drv_host);
     for (auto* v : {&c->prof_recs, &c->prof_pool})
         for (auto& r : *v) {
             (void)hipEventDestroy(r.e0);
@@ -761,6 +773,138 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     if (e != hipSuccess) {
         c->valid_len = saved;
         return fail(FDC_EHIP, "kernel launch failed: %s", hipGetErrorString(e));
+    }
+    return FDC_OK;
+}
+
+// Algorithm 1 end to end: one scheduler per scene, one forward pass per
+// iteration for the union of the ready sets, finishing decided on the host from
+// the tokens the pass produced.
+int32_t fdc_cot_decode(fdc_ctx* c, const int32_t* start_token, const int32_t* fixed_len,
+                       const int32_t* fixed_tok, const int32_t* eos_ids, int32_t n_eos,
+                       int32_t max_passes, int32_t* out_tok, int32_t* out_len, int32_t* out_passes,
+                       void* stream) {
+    if (!c) return fail(FDC_EINVAL, "null context");
+    if (!start_token || !out_tok || !out_len) return fail(FDC_EINVAL, "null pointer argument");
+    if (n_eos < 0 || (n_eos > 0 && !eos_ids)) return fail(FDC_EINVAL, "bad end-of-field token list");
+    if (!c->ws) return fail(FDC_ESTATE, "cache, workspace or head weights not set");
+    const int F = c->F, B = c->B, V = c->m.vocab;
+    const int Smax = *std::max_element(c->slot_len.begin(), c->slot_len.end());
+    std::vector<int32_t> fixed_at(F, 0);
+    {
+        int32_t at = 0;
+        for (int f = 0; f < F; ++f) {
+            const int n = fixed_len ? fixed_len[f] : 0;
+            if (n < 0 || n > c->slot_len[f]) return fail(FDC_ERANGE, "fixed_len[%d] = %d outside 0..%d", f, n, c->slot_len[f]);
+            if (n > 0 && !fixed_tok) return fail(FDC_EINVAL, "fixed_tok is null");
+            fixed_at[f] = at;
+            for (int i = 0; i < n; ++i)
+                if (fixed_tok[at + i] < 0 || fixed_tok[at + i] >= V)
+                    return fail(FDC_ERANGE, "token %d of fixed field %d outside the vocabulary", i, f);
+            if (n == 0 && (start_token[f] < 0 || start_token[f] >= V))
+                return fail(FDC_ERANGE, "start_token[%d] outside the vocabulary", f);
+            at += n;
+        }
+    }
+    hipStream_t st = (hipStream_t)stream;
+    struct Scheds {
+        std::vector<fdc_sched*> s;
+        ~Scheds() { for (fdc_sched* p : s) fdc_sched_destroy(p); }
+    } sch;
+    sch.s.assign(B, nullptr);
+    for (int b = 0; b < B; ++b) {
+        int32_t rc = fdc_sched_create(F, (int32_t)c->edge_src.size(), c->edge_src.data(), c->edge_dst.data(),
+                                      nullptr, &sch.s[b]);
+        if (rc != FDC_OK) return rc;
+    }
+    std::fill(out_tok, out_tok + (size_t)B * F * Smax, -1);
+    std::fill(out_len, out_len + (size_t)B * F, 0);
+    std::fill(c->valid_len.begin(), c->valid_len.end(), 0);      // every slot starts empty
+
+    int32_t* h_in = c->drv_host;
+    int32_t* h_out = c->drv_host + c->Mmax;
+    int32_t* d_in = c->at<int32_t>(c->off.tok_tmp);
+    int32_t* d_out = d_in + c->Mmax;
+    std::vector<int32_t> bf((size_t)B * c->Rmax), bo((size_t)B * c->Rmax);
+
+    // fixed template text: known from the start, so each such field is filled by
+    // multi-token passes (all scenes at once) before Algorithm 1 begins
+    int32_t fixed_passes = 0;
+    for (int f = 0; f < F; ++f) {
+        const int n = fixed_len ? fixed_len[f] : 0;
+        if (n == 0) continue;
+        for (int b = 0; b < B; ++b) {
+            int32_t rc = fdc_sched_complete(sch.s[b], f, n);
+            if (rc != FDC_OK) return fail(FDC_EINVAL, "fixed field %d depends on a field that is not fixed", f);
+        }
+        for (int t0 = 0; t0 < n; t0 += c->Tmax) {
+            const int T = std::min(c->Tmax, n - t0);
+            for (int b = 0; b < B; ++b) {
+                bf[b] = f;
+                bo[b] = t0;
+                for (int t = 0; t < T; ++t) h_in[b * T + t] = fixed_tok[fixed_at[f] + t0 + t];
+            }
+            FDC_HIP(hipMemcpyAsync(d_in, h_in, sizeof(int32_t) * B * T, hipMemcpyHostToDevice, st));
+            int32_t rc = fdc_parallel_decode_step(c, 1, T, bf.data(), bo.data(), d_in, nullptr, d_out, nullptr,
+                                                  nullptr, nullptr, stream);
+            if (rc != FDC_OK) return rc;
+            FDC_HIP(hipStreamSynchronize(st));                   // h_in is reused
+            ++fixed_passes;
+        }
+        for (int b = 0; b < B; ++b) {
+            out_len[(size_t)b * F + f] = n;
+            std::copy(fixed_tok + fixed_at[f], fixed_tok + fixed_at[f] + n, out_tok + ((size_t)b * F + f) * Smax);
+        }
+    }
+
+    std::vector<int32_t> last((size_t)B * F);
+    for (int b = 0; b < B; ++b) std::copy(start_token, start_token + F, last.begin() + (size_t)b * F);
+    std::vector<int32_t> pf((size_t)B * c->Rmax), po((size_t)B * c->Rmax), nact(B), fin(c->Rmax);
+    int32_t passes = 0;
+    for (;;) {
+        int R = 0;
+        for (int b = 0; b < B; ++b) {
+            int32_t rc = fdc_sched_peek(sch.s[b], c->Rmax, &pf[(size_t)b * c->Rmax], &po[(size_t)b * c->Rmax], &nact[b]);
+            if (rc != FDC_OK) return rc;
+            R = std::max(R, nact[b]);
+        }
+        if (R == 0) break;
+        if (max_passes > 0 && passes >= max_passes)
+            return fail(FDC_ECAP, "template not complete after %d passes", max_passes);
+        for (int b = 0; b < B; ++b)
+            for (int i = 0; i < R; ++i) {
+                const bool on = i < nact[b];
+                const int f = on ? pf[(size_t)b * c->Rmax + i] : -1;
+                bf[(size_t)b * R + i] = f;
+                bo[(size_t)b * R + i] = on ? po[(size_t)b * c->Rmax + i] : 0;
+                h_in[(size_t)b * R + i] = on ? last[(size_t)b * F + f] : 0;
+            }
+        FDC_HIP(hipMemcpyAsync(d_in, h_in, sizeof(int32_t) * B * R, hipMemcpyHostToDevice, st));
+        int32_t rc = fdc_parallel_decode_step(c, R, 1, bf.data(), bo.data(), d_in, nullptr, d_out, nullptr, nullptr,
+                                              nullptr, stream);
+        if (rc != FDC_OK) return rc;
+        FDC_HIP(hipMemcpyAsync(h_out, d_out, sizeof(int32_t) * B * R, hipMemcpyDeviceToHost, st));
+        FDC_HIP(hipStreamSynchronize(st));
+        // "the field corresponding to v is finished": the model ended the line,
+        // or the slot is full (truncation to the fixed length)
+        for (int b = 0; b < B; ++b) {
+            for (int i = 0; i < nact[b]; ++i) {
+                const int f = bf[(size_t)b * R + i], off = bo[(size_t)b * R + i];
+                const int32_t t = h_out[(size_t)b * R + i];
+                if (t < 0 || t >= V) return fail(FDC_EHIP, "pass %d produced token %d outside the vocabulary", passes, t);
+                out_tok[((size_t)b * F + f) * Smax + off] = t;
+                out_len[(size_t)b * F + f] = off + 1;
+                last[(size_t)b * F + f] = t;
+                fin[i] = off + 1 >= c->slot_len[f] || std::find(eos_ids, eos_ids + n_eos, t) != eos_ids + n_eos;
+            }
+            rc = fdc_sched_advance(sch.s[b], nact[b], fin.data());
+            if (rc != FDC_OK) return rc;
+        }
+        ++passes;
+    }
+    if (out_passes) {
+        out_passes[0] = passes;
+        out_passes[1] = fixed_passes;
     }
     return FDC_OK;
 }

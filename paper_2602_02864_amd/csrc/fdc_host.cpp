@@ -97,19 +97,20 @@ int32_t fdc_sched_create(int32_t F, int32_t E, const int32_t* src, const int32_t
                          const int32_t* content_len, fdc_sched** out) {
     if (!out) return fdc::fail(FDC_EINVAL, "null pointer argument");
     *out = nullptr;
-    if (F < 1 || !content_len) return fdc::fail(FDC_EINVAL, "bad field list");
+    if (F < 1) return fdc::fail(FDC_EINVAL, "bad field list");
     std::vector<int32_t> ones(F, 1), start(F);
     std::vector<uint64_t> anc((size_t)F * ((F + 63) / 64));
     int32_t total = 0;
     int32_t rc = fdc::build_plan(F, ones.data(), E, src, dst, 0, anc.data(), start.data(), nullptr, &total);
     if (rc != FDC_OK) return rc;
-    for (int f = 0; f < F; ++f)
-        if (content_len[f] < 1) return fdc::fail(FDC_EINVAL, "content_len[%d] = %d must be >= 1", f, content_len[f]);
+    if (content_len)
+        for (int f = 0; f < F; ++f)
+            if (content_len[f] < 1) return fdc::fail(FDC_EINVAL, "content_len[%d] = %d must be >= 1", f, content_len[f]);
     fdc_sched* s = new fdc_sched;
     s->F = F;
     s->indeg.assign(F, 0);
     s->done.assign(F, 0);
-    s->content_len.assign(content_len, content_len + F);
+    if (content_len) s->content_len.assign(content_len, content_len + F);
     s->succ.resize(F);
     s->ready.assign(F, 0);
     s->finished.assign(F, 0);
@@ -128,7 +129,17 @@ int32_t fdc_sched_create(int32_t F, int32_t E, const int32_t* src, const int32_t
 
 void fdc_sched_destroy(fdc_sched* s) { delete s; }
 
-int32_t fdc_sched_next(fdc_sched* s, int32_t max_branches, int32_t* branch_field,
+namespace {
+// a finished field leaves the ready set and signals its successors
+void retire(fdc_sched* s, int f) {
+    s->ready[f] = 0;
+    s->finished[f] = 1;
+    for (int u : s->succ[f])
+        if (--s->indeg[u] == 0) s->ready[u] = 1;
+}
+}  // namespace
+
+int32_t fdc_sched_peek(fdc_sched* s, int32_t max_branches, int32_t* branch_field,
                        int32_t* branch_off, int32_t* n_active) {
     if (!s || !branch_field || !branch_off || !n_active) return fdc::fail(FDC_EINVAL, "null pointer argument");
     int n = 0;
@@ -146,18 +157,54 @@ int32_t fdc_sched_next(fdc_sched* s, int32_t max_branches, int32_t* branch_field
         branch_off[j] = 0;
     }
     *n_active = n;
+    return FDC_OK;
+}
+
+int32_t fdc_sched_advance(fdc_sched* s, int32_t n, const int32_t* field_finished) {
+    if (!s || (n > 0 && !field_finished)) return fdc::fail(FDC_EINVAL, "null pointer argument");
+    std::vector<int32_t> act;
+    for (int f = 0; f < s->F; ++f)
+        if (s->ready[f]) act.push_back(f);
+    if (n != (int)act.size()) return fdc::fail(FDC_EINVAL, "%d flags for %d ready fields", n, (int)act.size());
     if (n == 0) return FDC_OK;
     s->passes++;
     s->tokens += n;
     // every ready field has decoded one token; finished ones release their successors
-    std::vector<int32_t> fin;
-    for (int f = 0; f < s->F; ++f)
-        if (s->ready[f] && ++s->done[f] >= s->content_len[f]) fin.push_back(f);
-    for (int f : fin) {
-        s->ready[f] = 0;
-        s->finished[f] = 1;
-        for (int u : s->succ[f])
-            if (--s->indeg[u] == 0) s->ready[u] = 1;
+    for (int i = 0; i < n; ++i) s->done[act[i]]++;
+    for (int i = 0; i < n; ++i)
+        if (field_finished[i]) retire(s, act[i]);
+    return FDC_OK;
+}
+
+int32_t fdc_sched_complete(fdc_sched* s, int32_t field, int32_t n_tokens) {
+    if (!s) return fdc::fail(FDC_EINVAL, "null pointer argument");
+    if (field < 0 || field >= s->F) return fdc::fail(FDC_ERANGE, "field %d outside 0..%d", field, s->F - 1);
+    if (n_tokens < 0) return fdc::fail(FDC_EINVAL, "negative token count");
+    if (!s->ready[field] || s->done[field] != 0)
+        return fdc::fail(FDC_EINVAL, "field %d is not an untouched ready field (its prerequisites must be complete)", field);
+    s->done[field] = n_tokens;
+    retire(s, field);
+    return FDC_OK;
+}
+
+int32_t fdc_sched_next(fdc_sched* s, int32_t max_branches, int32_t* branch_field,
+                       int32_t* branch_off, int32_t* n_active) {
+    if (s && s->content_len.empty()) return fdc::fail(FDC_EINVAL, "scheduler was created without content lengths");
+    int32_t rc = fdc_sched_peek(s, max_branches, branch_field, branch_off, n_active);
+    if (rc != FDC_OK || *n_active == 0) return rc;
+    std::vector<int32_t> fin(*n_active);
+    for (int i = 0; i < *n_active; ++i)
+        fin[i] = s->done[branch_field[i]] + 1 >= s->content_len[branch_field[i]];
+    return fdc_sched_advance(s, *n_active, fin.data());
+}
+
+int32_t fdc_sched_stats(const fdc_sched* s, int64_t* passes, int64_t* tokens, int32_t* n_unfinished) {
+    if (!s) return fdc::fail(FDC_EINVAL, "null pointer argument");
+    if (passes) *passes = s->passes;
+    if (tokens) *tokens = s->tokens;
+    if (n_unfinished) {
+        *n_unfinished = 0;
+        for (int f = 0; f < s->F; ++f) *n_unfinished += s->finished[f] ? 0 : 1;
     }
     return FDC_OK;
 }

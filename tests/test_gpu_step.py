@@ -285,3 +285,88 @@ def test_workload2_full_depth_first_passes():
         for i, (f, _) in enumerate(st):
             last[f] = int(ref["tok"][i])
     pair.close()
+
+
+def _driver_case(seed, header, D):
+    dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=D, d_mlp=160, vocab=520)
+    body = random_dag_template(1200 + seed, n_fields=6, prefix_len=21 + seed, max_slot=7, edge_prob=0.35,
+                               vocab=dims.vocab)
+    if header:      # field 0 is fixed template text that every other field depends on
+        tpl = random_dag_template(1200 + seed, n_fields=6, prefix_len=21 + seed, max_slot=7, edge_prob=0.35,
+                                  vocab=dims.vocab)
+        tpl.slot_len = [3] + body.slot_len
+        tpl.edges = [(0, v + 1) for v in range(6)] + [(u + 1, v + 1) for (u, v) in body.edges]
+        tpl.start_token = [0] + body.start_token
+        tpl.content_len = [3] + body.content_len
+        fixed = {0: [11, 7 + seed, 401]}
+    else:
+        tpl, fixed = body, None
+    return dims, tpl, fixed, draw_weights(40 + seed, dims, random_gains=True, std=0.05)
+
+
+@pytest.mark.parametrize("seed,B,header,D", [(57, 2, False, 64), (9, 3, True, 128)])
+def test_cot_decode_driver_matches_the_oracle_driver(seed, B, header, D):
+    """Algorithm 1 end to end on the GPU (free-running, end-of-line tokens, slot
+    truncation, scenes with different ready sets, fixed header text filled by
+    multi-token passes) against the oracle's driver: same tokens, same lengths,
+    same number of passes.  The seeds are ones where every top-2 gap of the oracle
+    run is well above the level at which greedy ids must agree."""
+    from tests.helpers import GAP_MIN
+    dims, tpl, fixed, w = _driver_case(seed, header, D)
+    F = tpl.n_fields
+    pair = Pair(dims, tpl, w, n_scenes=B, max_branches=F, max_tokens=2)
+    for b in range(B):
+        pair.prefill_with_oracle(b, draw_prefix_embeddings(40 + seed, tpl.prefix_len, dims.d_model, extra=b))
+    eos = list(range(0, dims.vocab, 3))
+    ref = O.run_cot_dynamic(pair.dec, tpl.start_token, eos, fixed)
+    assert ref["min_gap"] > 2 * GAP_MIN
+    got = pair.ctx.cot_decode(tpl.start_token, eos, fixed)
+    assert got["passes"] == ref["passes"]
+    assert got["fixed_passes"] == (2 if header else 0)          # 3 header tokens, 2 per pass
+    for b in range(B):
+        for f in range(F):
+            n = len(ref["text"][b][f])
+            assert got["len"][b, f] == n, (b, f)
+            assert list(got["tok"][b, f, :n]) == ref["text"][b][f], (b, f)
+            assert (got["tok"][b, f, n:] == -1).all()
+    assert np.array_equal(pair.ctx.get_valid_len(), pair.dec.valid_len)
+    lens = got["len"]
+    assert len({tuple(lens[b]) for b in range(B)}) > 1          # the scenes did diverge
+    # a second run starts from empty slots again and repeats itself
+    again = pair.ctx.cot_decode(tpl.start_token, eos, fixed)
+    assert np.array_equal(again["tok"], got["tok"]) and again["passes"] == got["passes"]
+    # without end tokens every generated field runs to its slot length
+    full = pair.ctx.cot_decode(tpl.start_token, (), fixed)
+    assert np.array_equal(full["len"], np.tile(np.asarray(tpl.slot_len, dtype=np.int32), (B, 1)))
+    cp = [0] * F
+    for f in range(F):
+        cp[f] = (0 if fixed and f in fixed else tpl.slot_len[f]) + \
+            max([cp[u] for (u, v) in tpl.edges if v == f], default=0)
+    assert full["passes"] == max(cp)
+    pair.close()
+
+
+def test_cot_decode_driver_error_paths():
+    import paper_2602_02864_amd.binding as fb
+    dims, tpl, fixed, w = _driver_case(9, True, 64)
+    F = tpl.n_fields
+    pair = Pair(dims, tpl, w, n_scenes=1, max_branches=F, max_tokens=2)
+    pair.prefill_with_oracle(0, draw_prefix_embeddings(49, tpl.prefix_len, dims.d_model))
+
+    def code(*a, **k):
+        with pytest.raises(fb.FdcError) as e:
+            pair.ctx.cot_decode(*a, **k)
+        return e.value.code
+    assert code(tpl.start_token, (), fixed, max_passes=2) == fb.FDC_ECAP
+    bad = list(tpl.start_token)
+    bad[2] = dims.vocab
+    assert code(bad, (), fixed) == fb.FDC_ERANGE
+    assert code(tpl.start_token, (), {0: [1, 2, 3, 4]}) == fb.FDC_ERANGE       # longer than the slot
+    assert code(tpl.start_token, (), {0: [1, dims.vocab]}) == fb.FDC_ERANGE
+    assert code(tpl.start_token, (), {1: [5]}) == fb.FDC_EINVAL                # depends on the unfixed field 0
+    pair.close()
+    narrow = Pair(dims, tpl, w, n_scenes=1, max_branches=1, max_tokens=2)      # ready sets larger than R
+    with pytest.raises(fb.FdcError) as e:
+        narrow.ctx.cot_decode(tpl.start_token, (), fixed)
+    assert e.value.code == fb.FDC_ECAP
+    narrow.close()

@@ -116,6 +116,68 @@ def test_scheduler_matches_oracle_algorithm1(seed):
     assert e.value.code == fb.FDC_ECYCLE
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_dynamic_scheduler_follows_algorithm1_under_random_finishing(seed):
+    """peek / advance with finishing decided by the caller: the ready sets are
+    those of Algorithm 1 written out with in-degree counters and a set, for any
+    sequence of finishing decisions; pre-filled fields release their successors."""
+    from paper_2602_02864_amd import Scheduler
+    rng = np.random.default_rng(900 + seed)
+    tpl = random_dag_template(800 + seed, n_fields=3 + 2 * seed, prefix_len=0, max_slot=7,
+                              edge_prob=0.3, vocab=10)
+    F = tpl.n_fields
+    preds = [set(u for (u, v) in tpl.edges if v == f) for f in range(F)]
+    fixed = {}
+    if seed % 2:                        # roots as fixed text
+        fixed = {f: int(rng.integers(1, 5)) for f in range(F) if not preds[f] and rng.random() < 0.6}
+    s = Scheduler(F, tpl.edges)
+    for f in sorted(fixed):
+        s.complete(f, fixed[f])
+    d = [len(preds[f] - set(fixed)) for f in range(F)]
+    S = {f for f in range(F) if d[f] == 0 and f not in fixed}
+    done = [0] * F
+    passes = tokens = 0
+    while True:
+        bf, bo = s.peek()
+        assert list(bf) == sorted(S) and list(bo) == [done[f] for f in sorted(S)]
+        if not S:
+            break
+        fin = [int(rng.random() < 0.4) for _ in bf]
+        s.advance(fin)
+        passes += 1
+        tokens += len(bf)
+        for f, fl in zip(sorted(S), fin):
+            done[f] += 1
+            if fl:
+                S.discard(f)
+                for u in range(F):
+                    if f in preds[u]:
+                        d[u] -= 1
+                        if d[u] == 0:
+                            S.add(u)
+    assert s.stats() == {"passes": passes, "tokens": tokens, "unfinished": 0}
+    with pytest.raises(FdcError) as e:
+        s.advance([1])                                   # nothing is ready any more
+    assert e.value.code == fb.FDC_EINVAL
+    s.close()
+    s = Scheduler(3, [(0, 1), (1, 2)])
+    with pytest.raises(FdcError) as e:
+        s.complete(1, 2)                                 # its prerequisite is not complete
+    assert e.value.code == fb.FDC_EINVAL
+    with pytest.raises(FdcError) as e:
+        s.complete(3, 1)
+    assert e.value.code == fb.FDC_ERANGE
+    bf, _ = s.peek()
+    with pytest.raises(FdcError) as e:
+        s.advance([0, 0])                                # one field is ready, two flags
+    assert e.value.code == fb.FDC_EINVAL
+    with pytest.raises(FdcError) as e:
+        fb._check(fb.lib().fdc_sched_next(s._h, 3, fb._p(np.zeros(3, np.int32)), fb._p(np.zeros(3, np.int32)),
+                                          fb._p(np.zeros(1, np.int32))))
+    assert e.value.code == fb.FDC_EINVAL                 # created without content lengths
+    s.close()
+
+
 def test_build_mask_error_codes():
     def code(*a):
         with pytest.raises(FdcError) as e:
@@ -154,4 +216,7 @@ def test_null_pointers_are_rejected_not_dereferenced():
     assert L.fdc_argmax(None, 1, 1, 1, None, None, None) == fb.FDC_EINVAL
     assert L.fdc_kv_append(None, 0, None, None, None, None, 0, None) == fb.FDC_EINVAL
     assert L.fdc_parallel_decode_step(None, 1, 1, None, None, None, None, None, None, None, None, None) == fb.FDC_EINVAL
+    assert L.fdc_cot_decode(None, None, None, None, None, 0, 0, None, None, None, None) == fb.FDC_EINVAL
+    assert L.fdc_sched_peek(None, 1, None, None, None) == fb.FDC_EINVAL
+    assert L.fdc_sched_advance(None, 0, None) == fb.FDC_EINVAL
     assert L.fdc_packed_weight_bytes(16, 32) == 1024 and L.fdc_packed_weight_bytes(1000, 32) == 1008 * 64

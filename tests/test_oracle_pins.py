@@ -488,3 +488,130 @@ def test_run_cot_free_running_matches_manual_feedback():
                 assert st["tok_in"][i] == first[f]
             first[f] = int(st["out"]["tok"][i])
     assert list(dec.valid_len[0]) == tpl.content_len
+
+
+# ------------------------------------- Algorithm 1 with real finishing rules
+def _tiny_decoder(tpl, seed_cfg, B=1):
+    w, _ = _tiny_setup(tpl, seed_cfg=seed_cfg)
+    dec = O.OracleDecoder(TINY, w, tpl.prefix_len, tpl.slot_len, tpl.edges, n_scenes=B)
+    for b in range(B):
+        dec.prefill_prefix(b, draw_prefix_embeddings(seed_cfg + 31 * b, tpl.prefix_len, TINY.d_model)
+                           .astype(np.float64))
+    return w, dec
+
+
+def _texts_from_trace(trace, F):
+    text = [[] for _ in range(F)]
+    for st in trace:
+        for i, f in enumerate(st["branch_field"]):
+            if f >= 0:
+                text[f].append(int(st["out"]["tok"][i]))
+    return text
+
+
+def test_dynamic_driver_without_end_tokens_fills_every_slot():
+    """No end token: every field is truncated at its slot length (Sec. 3.3), so the
+    run is the static schedule with content_len = slot_len, pass for pass."""
+    tpl = random_dag_template(33, n_fields=5, prefix_len=3, max_slot=4, edge_prob=0.4, vocab=TINY.vocab)
+    _, dec = _tiny_decoder(tpl, 9)
+    res = O.run_cot_dynamic(dec, tpl.start_token)
+    assert [len(t) for t in res["text"][0]] == tpl.slot_len
+    assert res["passes"] == _critical_path(5, tpl.edges, tpl.slot_len)
+    _, dec2 = _tiny_decoder(tpl, 9)
+    assert res["text"][0] == _texts_from_trace(O.run_cot(dec2, tpl.slot_len, tpl.start_token), 5)
+    assert list(dec.valid_len[0]) == tpl.slot_len
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_dynamic_driver_end_tokens_finish_fields_and_passes_are_minimal(seed):
+    """A field ends at its first end token or at its slot length; the number of
+    passes is the critical path of the lengths that came out (Sec. 3.2:
+    optimal), and the tokens are those of the static schedule for those lengths."""
+    tpl = random_dag_template(50 + seed, n_fields=6, prefix_len=2, max_slot=5, edge_prob=0.35,
+                              vocab=TINY.vocab)
+    eos = set(range(0, TINY.vocab, 3))                        # a third of the vocabulary ends a line
+    _, dec = _tiny_decoder(tpl, 11 + seed)
+    res = O.run_cot_dynamic(dec, tpl.start_token, eos)
+    text = res["text"][0]
+    lens = [len(t) for t in text]
+    for f, t in enumerate(text):
+        assert 1 <= len(t) <= tpl.slot_len[f]
+        assert not any(x in eos for x in t[:-1])
+        assert t[-1] in eos or len(t) == tpl.slot_len[f]
+    assert res["passes"] == _critical_path(6, tpl.edges, lens)
+    assert list(dec.valid_len[0]) == lens
+    _, dec2 = _tiny_decoder(tpl, 11 + seed)
+    assert text == _texts_from_trace(O.run_cot(dec2, lens, tpl.start_token), 6)
+    if seed == 0:
+        assert len(set(lens)) > 1 and any(l < s for l, s in zip(lens, tpl.slot_len))
+
+
+def test_dynamic_driver_on_a_chain_is_greedy_autoregressive_decoding_with_stop_tokens():
+    """Chain-shaped graph = the autoregressive baseline (Sec. 4.1): compared with a
+    plain causal decoder that re-reads the whole sequence for every token."""
+    F, S, P = 3, 4, 4
+    tpl = chain_template(F, S, P, TINY.vocab)
+    w, dec = _tiny_decoder(tpl, 13)
+    prefix = draw_prefix_embeddings(13, P, TINY.d_model).astype(np.float64)
+    eos = set(range(1, TINY.vocab, 4))
+    res = O.run_cot_dynamic(dec, tpl.start_token, eos)
+    emb = np.asarray(w["emb"], dtype=np.float64)
+    rows, pos, want = [r for r in prefix], list(range(P)), []
+    for f in range(F):
+        tok, out = tpl.start_token[f], []
+        for o in range(S):
+            rows.append(emb[tok])
+            pos.append(P + f * S + o)
+            logits, _ = _torch_reference_logits(TINY, w, np.array(rows), np.array(pos))
+            tok = int(np.argmax(logits[-1]))
+            out.append(tok)
+            if tok in eos:
+                break
+        want.append(out)
+    assert res["text"][0] == want
+    assert res["passes"] == sum(len(t) for t in want)
+
+
+def test_dynamic_driver_scenes_diverge_and_stay_independent():
+    """Sec. 3.2: field lengths differ from case to case, so scenes sharing a
+    pass have different ready sets; each scene's result is that of running it alone."""
+    tpl = random_dag_template(77, n_fields=5, prefix_len=3, max_slot=5, edge_prob=0.4, vocab=TINY.vocab)
+    eos = set(range(0, TINY.vocab, 3))
+    w, dec = _tiny_decoder(tpl, 17, B=2)
+    res = O.run_cot_dynamic(dec, tpl.start_token, eos)
+    alone = []
+    for b in range(2):
+        d1 = O.OracleDecoder(TINY, w, tpl.prefix_len, tpl.slot_len, tpl.edges)
+        d1.prefill_prefix(0, draw_prefix_embeddings(17 + 31 * b, tpl.prefix_len, TINY.d_model).astype(np.float64))
+        alone.append(O.run_cot_dynamic(d1, tpl.start_token, eos))
+        assert res["text"][b] == alone[b]["text"][0]
+    assert res["text"][0] != res["text"][1]
+    assert res["passes"] == max(a["passes"] for a in alone)
+    assert any((p["branch_field"][0] != p["branch_field"][1]).any() for p in res["trace"])
+
+
+def test_dynamic_driver_fixed_text_is_visible_like_a_longer_prefix():
+    """Sec. 3.3: fixed template tokens are pre-filled and visible to every later
+    token.  A header field that every other field depends on and whose slot it
+    fills must act exactly like the same tokens appended to the prefix."""
+    P, H = 3, 2
+    body = random_dag_template(91, n_fields=4, prefix_len=P + H, max_slot=4, edge_prob=0.4, vocab=TINY.vocab)
+    header = [7, 19]
+    edges = [(0, v + 1) for v in range(4)] + [(u + 1, v + 1) for (u, v) in body.edges]
+    slot_len = [H] + body.slot_len
+    start = [0] + body.start_token
+    eos = set(range(2, TINY.vocab, 3))
+    w, _ = _tiny_setup(body, seed_cfg=19)
+    prefix = draw_prefix_embeddings(19, P, TINY.d_model).astype(np.float64)
+    dec = O.OracleDecoder(TINY, w, P, slot_len, edges)
+    dec.prefill_prefix(0, prefix)
+    res = O.run_cot_dynamic(dec, start, eos, fixed={0: header})
+    assert res["text"][0][0] == header
+    ref = O.OracleDecoder(TINY, w, P + H, body.slot_len, body.edges)
+    emb = np.asarray(w["emb"], dtype=np.float64)
+    ref.prefill_prefix(0, np.concatenate([prefix, emb[header]]))
+    want = O.run_cot_dynamic(ref, body.start_token, eos)
+    assert res["text"][0][1:] == want["text"][0]
+    assert res["passes"] == want["passes"]
+    with pytest.raises(ValueError):
+        O.run_cot_dynamic(dec, start, eos, fixed={1: [3]})     # field 1 depends on the unfixed field 0
