@@ -188,6 +188,8 @@ def run_decode(args, cfg_id, chain=False):
         "kernels": kernels,
         "host_wall_ms_per_step": round(1e3 * t_wall / K, 4),
     }
+    if not args.no_driver and args.steps == 0:
+        res["driver"] = run_driver(ctx, dims, tpl, torch)
     if args.prefill:
         # the prefix as field 0 of a context over the same cache: causal prefill by
         # the same step, `chunk` embedding rows per pass (the paper's "CoT time" also
@@ -207,6 +209,34 @@ def run_decode(args, cfg_id, chain=False):
         view.close()
     ctx.close()
     return res
+
+
+def run_driver(ctx, dims, tpl, torch, every=40):
+    """The whole template decoded by the library's own Algorithm 1 loop
+    (fdc_cot_decode): fields end when the model emits an end-of-line token or the
+    slot is full, so the schedule is not known beforehand and every pass ends with
+    the produced tokens read back by the host.  A random-init model has no
+    end-of-line token: one token id in `every` is declared to be one, which gives
+    field lengths of about that many tokens, cut at the slot length."""
+    from paper_2602_02864_amd import Context
+    F = tpl.n_fields
+    # ready sets of a run with unknown lengths can mix levels: room for every field
+    drv = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, 1, F, 1, share=ctx)
+    eos = list(range(0, dims.vocab, every))
+    out = None
+    for rep in range(2):                  # the first run warms up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = drv.cot_decode(tpl.start_token, eos)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    drv.close()
+    tokens, passes = int(out["len"].sum()), out["passes"]
+    return {"entry": "fdc_cot_decode", "end_of_line": f"token id % {every} == 0, or the slot is full",
+            "passes": passes, "tokens": tokens, "tokens_per_pass": round(tokens / passes, 3),
+            "ms_per_pass": round(1e3 * dt / passes, 4), "tokens_per_s": round(tokens / dt, 1),
+            "field_lengths": [int(x) for x in out["len"][0]],
+            "note": "host wall clock over the whole loop, one stream synchronisation per pass"}
 
 
 MFMA_PEAK_TFLOPS = 2500.0
@@ -472,6 +502,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-ar", action="store_true", help="skip the autoregressive (chain graph) baseline")
+    ap.add_argument("--no-driver", action="store_true", help="skip the run of the library's own Algorithm 1 loop")
     ap.add_argument("--prefill", action="store_true", help="also time the causal prefill of the prefix")
     ap.add_argument("--single", action="store_true", help="cfg3: only --rho, no sweep over densities")
     args = ap.parse_args()
