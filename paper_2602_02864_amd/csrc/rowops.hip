@@ -139,23 +139,34 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta s
     const int m = blockIdx.y;
     const int br = m / sm.T, t = m % sm.T;
     const int f = sm.branch_field[br];
-    if (f < 0) return;
-    const int scene = br / sm.R;
-    const int pos = sm.slot_start[f] + sm.branch_off[br] + t;
     const int Nqkv = (a.Hq + 2 * a.Hkv) * D;
     constexpr int half = D / 2;
     const int n_pairs = (a.Hq + a.Hkv) * half;
     const int n_v2 = a.Hkv * D / 2;
     const int item = blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_pairs + n_v2) return;
+    const bool rot = item < n_pairs;
+    // The two elements this thread owns: a rotary pair (i, i + D/2) of a Q or K
+    // head, or two neighbouring V elements.  Their split-K partials do not
+    // depend on the branch tables, so they are requested before the (dependent)
+    // look-ups of field, slot start and rotation, and inactive rows read theirs
+    // for nothing (the rows exist in the workspace).
+    const int hd = item / half, i = item % half;
+    const int e = 2 * (item - n_pairs);
+    const int c1 = rot ? hd * D + i : (a.Hq + a.Hkv) * D + e;
+    const int c2 = rot ? c1 + half : c1 + 1;
     const float* __restrict__ part = a.part + (size_t)m * Nqkv;
     const size_t sstride = (size_t)a.M * Nqkv;
-    if (item < n_pairs) {
-        const int hd = item / half, i = item % half;
-        float x1 = 0.f, x2 = 0.f;
-        for (int s = 0; s < a.S; ++s) {
-            x1 += part[s * sstride + hd * D + i];
-            x2 += part[s * sstride + hd * D + i + half];
-        }
+    float x1 = 0.f, x2 = 0.f;
+#pragma unroll 4
+    for (int s = 0; s < a.S; ++s) {
+        x1 += part[s * sstride + c1];
+        x2 += part[s * sstride + c2];
+    }
+    if (f < 0) return;
+    const int scene = br / sm.R;
+    const int pos = sm.slot_start[f] + sm.branch_off[br] + t;
+    if (rot) {
         const float2 cssn = a.tab[(size_t)pos * half + i];
         const float y1 = x1 * cssn.x - x2 * cssn.y, y2 = x2 * cssn.x + x1 * cssn.y;
         if (hd < a.Hq) {
@@ -167,16 +178,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta s
             cache_store<D>(a.kc, a.vc, scene, kvh, a.Hkv, a.NB, pos, i, true, f2bf(y1));
             cache_store<D>(a.kc, a.vc, scene, kvh, a.Hkv, a.NB, pos, i + half, true, f2bf(y2));
         }
-    } else if (item < n_pairs + n_v2) {
-        const int e = 2 * (item - n_pairs);
-        const int voff = (a.Hq + a.Hkv) * D;
-        float v0 = 0.f, v1 = 0.f;
-        for (int s = 0; s < a.S; ++s) {
-            v0 += part[s * sstride + voff + e];
-            v1 += part[s * sstride + voff + e + 1];
-        }
-        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D, false, f2bf(v0));
-        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D + 1, false, f2bf(v1));
+    } else {
+        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D, false, f2bf(x1));
+        cache_store<D>(a.kc, a.vc, scene, e / D, a.Hkv, a.NB, pos, e % D + 1, false, f2bf(x2));
     }
 }
 
@@ -226,8 +230,7 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     }
     const float* row = logits + (size_t)m * ld;
     Top2 t{-INFINITY, -INFINITY, 0x7fffffff};
-    for (int v = threadIdx.x; v < V; v += blockDim.x) {
-        const float x = row[v];
+    auto push = [&](float x, int v) {
         if (x > t.m1) {
             t.m2 = t.m1;
             t.m1 = x;
@@ -235,6 +238,31 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
         } else if (x > t.m2) {
             t.m2 = x;
         }
+    };
+    if ((reinterpret_cast<uintptr_t>(row) & 15) == 0) {
+        // 16-byte loads, eight per thread in flight: the row comes in about one
+        // round trip instead of one per element
+        const int V4 = V >> 2;
+        constexpr int U = 8;
+        for (int v0 = threadIdx.x; v0 < V4; v0 += U * blockDim.x) {
+            float4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int v4 = v0 + u * blockDim.x;
+                x[u] = v4 < V4 ? reinterpret_cast<const float4*>(row)[v4] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int v = 4 * (v0 + u * blockDim.x);
+                push(x[u].x, v);
+                push(x[u].y, v + 1);
+                push(x[u].z, v + 2);
+                push(x[u].w, v + 3);
+            }
+        }
+        for (int v = 4 * V4 + threadIdx.x; v < V; v += blockDim.x) push(row[v], v);
+    } else {
+        for (int v = threadIdx.x; v < V; v += blockDim.x) push(row[v], v);
     }
     for (int o = 32; o > 0; o >>= 1) {
         Top2 u{__shfl_xor(t.m1, o), __shfl_xor(t.m2, o), __shfl_xor(t.i1, o)};
