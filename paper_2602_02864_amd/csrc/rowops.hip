@@ -30,14 +30,17 @@ template <int NT, int VEC>
 __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm) {
     __shared__ float sh[NT / 64];
     const int m = blockIdx.x;
-    const bool active = sm.branch_field == nullptr || sm.branch_field[m / sm.T] >= 0;
+    // whether the row is active is looked at only after its data has been
+    // requested: rows of inactive branches exist in every buffer, are read for
+    // nothing and come out as zeros
+    const int field = sm.branch_field ? sm.branch_field[m / sm.T] : 0;
     const int nvec = a.d >> 2;
     f32x4 v[VEC];
     const float* __restrict__ xin = a.x + (size_t)m * a.d;
     const float* __restrict__ part = a.part;
     const uint16_t* __restrict__ erow = nullptr;
     if (a.tok) {
-        int t = active ? a.tok[m] : 0;
+        int t = a.tok[m];
         t = t < 0 ? 0 : (t >= a.vocab ? a.vocab - 1 : t);
         erow = a.emb + (size_t)t * a.d;
     } else if (a.emb_rows) {
@@ -47,7 +50,7 @@ __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm)
     for (int i = 0; i < VEC; ++i) {
         const int q = threadIdx.x + i * NT;
         v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (q < nvec && active) {
+        if (q < nvec) {
             if (erow) {
                 const uint2 e = *reinterpret_cast<const uint2*>(erow + 4 * q);
                 v[i] = f32x4{__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xffff0000u),
@@ -57,11 +60,14 @@ __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm)
             }
         }
     }
-    if (!erow && active) {
-        for (int s0 = 0; s0 < a.S; s0 += 8) {
-            f32x4 p[8][VEC];
+    if (!erow) {
+        // eight partials in flight per thread: the row's partials arrive at the rate
+        // one compute unit can take them in, more in flight does not help
+        constexpr int PB = 8;
+        for (int s0 = 0; s0 < a.S; s0 += PB) {
+            f32x4 p[PB][VEC];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < PB; ++j) {
                 const int s = min(s0 + j, a.S - 1);            // past the end: a repeat, not added
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) {
@@ -71,7 +77,7 @@ __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm)
                 }
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < PB; ++j)
                 if (s0 + j < a.S)
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) v[i] += p[j][i];
@@ -84,6 +90,9 @@ __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm)
         const int q = threadIdx.x + i * NT;
         gain[i] = q < nvec ? *reinterpret_cast<const f32x4*>(a.gain + 4 * q) : f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    if (field < 0)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < VEC; ++i) ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
