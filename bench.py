@@ -194,7 +194,7 @@ def run_decode(args, cfg_id, chain=False):
         # the prefix as field 0 of a context over the same cache: causal prefill by
         # the same step, `chunk` embedding rows per pass (the paper's "CoT time" also
         # counts this input processing, Sec. 4.1; the decode figure above does not)
-        chunk, P = 128, tpl.prefix_len
+        chunk, P = args.prefill_chunk, tpl.prefix_len
         view = ctx.prefill_view(chunk)
         emb = torch.randn(1, P, dims.d_model, device=dev, generator=g).to(torch.bfloat16)
         for rep in range(2):
@@ -504,6 +504,7 @@ def main():
     ap.add_argument("--no-ar", action="store_true", help="skip the autoregressive (chain graph) baseline")
     ap.add_argument("--no-driver", action="store_true", help="skip the run of the library's own Algorithm 1 loop")
     ap.add_argument("--prefill", action="store_true", help="also time the causal prefill of the prefix")
+    ap.add_argument("--prefill-chunk", type=int, default=1024, help="prefix tokens per prefill pass (at most 1024)")
     ap.add_argument("--single", action="store_true", help="cfg3: only --rho, no sweep over densities")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
