@@ -132,21 +132,67 @@ __device__ __forceinline__ float other_half(float x, int hh) {
     return __uint_as_float(hh ? r[0] : r[1]);
 }
 
+// Visibility words of one step: for every scene b, every 32-key tile t that
+// reaches past the prefix and every branch-token row j (branch r, token tt:
+// j = r * T + tt) the 32 bits "key k of the tile is visible to that row".  A
+// row of field f at slot offset o sees what is left of the prefix in the tile,
+// the first valid_len[g] keys of each strict ancestor slot g and the first o+1
+// keys of its own slot (Sec. 3.3; Eq. 1).  The words depend on the step only,
+// not on the layer or the head: they are built once per step and every
+// attention workgroup of every layer fetches the few it needs.
+__global__ __launch_bounds__(256) void mask_words_kernel(StepMeta sm, const uint64_t* __restrict__ anc, int P,
+                                                         int n_tiles, uint32_t* __restrict__ words) {
+    const int RT = sm.R * sm.T;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= sm.B * n_tiles * RT) return;
+    const int j = idx % RT, t = (idx / RT) % n_tiles, b = idx / (RT * n_tiles);
+    const int r = j / sm.T, tt = j % sm.T;
+    const int f = sm.branch_field[b * sm.R + r];
+    uint32_t bits = 0;
+    if (f >= 0) {
+        const int off = sm.branch_off[b * sm.R + r] + tt;
+        const int key0 = ((P >> 5) + t) * 32;
+        if (key0 < P) {
+            const int nb = min(P - key0, 32);
+            bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
+        }
+        const unsigned long long av = anc[f];
+        for (int g = 0; g < sm.F; ++g) {             // slots are laid out in field order
+            const int s0 = sm.slot_start[g];
+            if (s0 >= key0 + 32) break;
+            // keys of slot g this row sees: its own up to its token, an ancestor's all written
+            const int n = g == f ? off + 1 : ((av >> g) & 1ull) ? sm.valid_len[b * sm.F + g] : 0;
+            const int lo = max(s0, key0), hi = min(s0 + n, key0 + 32);
+            if (hi > lo) {
+                const int nb = hi - lo;
+                bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
+            }
+        }
+    }
+    words[idx] = bits;
+}
+
 // QF32: the queries come in fp32 (inside the decode step) and are used as bf16
 // head + tail; otherwise they are bf16 data and have no tail.
 // Start-up tables of a workgroup: its rows, and for the tiles of its chunk that
 // reach past the prefix one 32-key visibility word per (tile, row) plus their
-// OR per tile.  Everything read from memory (branch tables, slot starts, valid
-// lengths, ancestor words) is fetched in one round trip; the words are computed
-// once per branch row (the G query heads of a branch token share them) and then
+// OR per tile.  Everything read from memory (branch tables, the step's
+// visibility words) is fetched in one round trip; the words exist once per
+// branch-token row (the G query heads of a branch token share them) and are
 // copied to the rows.  Ends with a barrier.
 template <int NR, int NT>
 __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& sm, int b, int kvh, int rg, int mt0,
                                              int nmt, int* row_m, int* row_head, int* row_field, int* row_off,
-                                             int* s_start, int* vlen, unsigned long long* anc_l,
                                              uint32_t (*bmask)[NR], uint32_t (*rowmask)[NR], uint32_t* tile_any) {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int F = sm.F;
+    const int tid = threadIdx.x;
+    // branch-token rows of this row group: jr = (rg * NR + r) / G
+    const int RT = sm.R * sm.T;
+    const int jr0 = (rg * NR) / a.G, nbr = (rg * NR + NR - 1) / a.G - jr0 + 1;
+    const uint32_t* __restrict__ words = a.mask_words + ((size_t)b * a.mw_tiles + (mt0 - (a.P >> 5))) * RT;
+    for (int idx = tid; idx < nmt * nbr; idx += NT) {
+        const int t = idx / nbr, j = idx % nbr;
+        bmask[t][j] = jr0 + j < RT ? words[(size_t)t * RT + jr0 + j] : 0u;
+    }
     for (int r = tid; r < NR; r += NT) {
         const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
         row_m[r] = ri.m;
@@ -154,50 +200,14 @@ __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& 
         row_field[r] = ri.field;
         row_off[r] = ri.off;
     }
-    if (nmt > 0) {                                    // uniform: the chunk reaches into the slots
-        for (int g = tid; g < F; g += NT) {
-            s_start[g] = sm.slot_start[g];
-            vlen[g] = sm.valid_len[b * F + g];
-            anc_l[g] = a.anc[g];
-        }
-        for (int t = tid; t < nmt; t += NT) tile_any[t] = 0u;
-    }
+    for (int t = tid; t < nmt; t += NT) tile_any[t] = 0u;
     __syncthreads();
     if (nmt > 0) {
-        // branch rows of this row group: jr = (rg * NR + r) / G
-        const int jr0 = (rg * NR) / a.G, nbr = (rg * NR + NR - 1) / a.G - jr0 + 1;
-        for (int idx = tid; idx < nmt * nbr; idx += NT) {
-            const int t = idx / nbr, j = idx % nbr;
-            const int r = max(0, (jr0 + j) * a.G - rg * NR);      // a row of that branch row
-            const int key0 = (mt0 + t) * 32;
-            const int f = row_field[r];
-            uint32_t bits = 0;
-            if (row_m[r] >= 0) {
-                if (key0 < a.P) {
-                    const int nb = min(a.P - key0, 32);
-                    bits = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                }
-                const unsigned long long anc = anc_l[f];
-                for (int g = 0; g < F; ++g) {            // slots are laid out in field order
-                    if (g + 1 < F && s_start[g + 1] <= key0) continue;     // ends before the tile
-                    const int s0 = s_start[g];
-                    if (s0 >= key0 + 32) break;
-                    // keys of slot g this row sees: its own up to its token, an ancestor's all written
-                    const int n = g == f ? row_off[r] + 1 : ((anc >> g) & 1ull) ? vlen[g] : 0;
-                    const int lo = max(s0, key0), hi = min(s0 + n, key0 + 32);
-                    if (hi > lo) {
-                        const int nb = hi - lo;
-                        bits |= (nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u)) << (lo - key0);
-                    }
-                }
-                if (bits) atomicOr(&tile_any[t], bits);
-            }
-            bmask[t][j] = bits;
-        }
-        __syncthreads();
         for (int idx = tid; idx < nmt * NR; idx += NT) {
             const int t = idx / NR, r = idx % NR;
-            rowmask[t][r] = row_m[r] >= 0 ? bmask[t][(rg * NR + r) / a.G - jr0] : 0u;
+            const uint32_t bits = row_m[r] >= 0 ? bmask[t][(rg * NR + r) / a.G - jr0] : 0u;
+            rowmask[t][r] = bits;
+            if (bits) atomicOr(&tile_any[t], bits);
         }
     }
     __syncthreads();
@@ -214,8 +224,6 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t tile_any[kMaxMaskedTiles];
     __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
-    __shared__ int s_start[kMaxFields], vlen[kMaxFields];
-    __shared__ unsigned long long anc_l[kMaxFields];
     __shared__ uint16_t act_list[kStreams][kMaxChunkTiles / kStreams];
     __shared__ int n_act[kStreams];
     __shared__ float xm[NR], xl[NR];
@@ -230,9 +238,35 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     const int mt0 = max(cb0, a.P >> 5);             // first tile of the chunk that reaches past the prefix
     const int nmt = max(0, blk_end - mt0);
 
-    // ---- start-up: rows, per-slot visible counts, visibility words, tile lists ---
-    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, s_start, vlen, anc_l,
-                         bmask, rowmask, tile_any);
+    // The query rows are requested first: where a row of the group lives (step
+    // row m, head) follows from the launch shape alone; whether its branch is
+    // active is known only after the tables and decides below if it is used.
+    // row rt*32 + lane%32, d = 16*j + 8*(lane/32) + 0..7
+    f32x4 qraw[QF32 ? DJ : 1][2];
+    bf16x8 qb[QF32 ? 1 : DJ];
+    {
+        const int gr = rg * NR + rt * 32 + r32;
+        const int jr = gr / a.G, ridx = jr / sm.T;
+        const bool exists = ridx < sm.R;
+        const int m = exists ? (b * sm.R + ridx) * sm.T + jr % sm.T : 0;
+        const size_t qo = ((size_t)m * a.Hq + kvh * a.G + gr % a.G) * D + 8 * hh;
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) {
+            if (QF32) {
+                qraw[j][0] = qraw[j][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (exists) {
+                    qraw[j][0] = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 16 * j);
+                    qraw[j][1] = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 16 * j + 4);
+                }
+            } else {
+                qb[j] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                if (exists) qb[j] = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo + 16 * j);
+            }
+        }
+    }
+
+    // ---- start-up: rows, visibility words, tile lists ---
+    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, bmask, rowmask, tile_any);
     if (wave < kStreams) {
         // candidates of stream w: tiles cb0 + w, cb0 + w + 2, ...; keep the visible ones
         const int blk = cb0 + wave + kStreams * lane;
@@ -248,30 +282,21 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     // lane j keeps the j-th active tile of this stream (read back with readlane)
     const int my_tiles = lane < n_mine ? (int)act_list[strm][lane] : 0;
 
-    // query operand in registers: row rt*32 + lane%32, d = 16*j + 8*(lane/32) + 0..7
+    // query operand in registers (zero for rows of inactive branches)
     Frag qh[DJ], ql[QF32 ? DJ : 1];
     {
-        const int r = rt * 32 + r32;
-        const int m = row_m[r];
+        const bool act = row_m[rt * 32 + r32] >= 0;
 #pragma unroll
         for (int j = 0; j < DJ; ++j) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                qh[j].u[k] = 0;
-                if (QF32) ql[j].u[k] = 0;
-            }
-            if (m >= 0) {
-                const size_t qo = ((size_t)m * a.Hq + row_head[r]) * D + 16 * j + 8 * hh;
-                if (QF32) {
-                    const f32x4 q0 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo);
-                    const f32x4 q1 = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 4);
-                    split2(q0[0], q0[1], qh[j].u[0], ql[j].u[0]);
-                    split2(q0[2], q0[3], qh[j].u[1], ql[j].u[1]);
-                    split2(q1[0], q1[1], qh[j].u[2], ql[j].u[2]);
-                    split2(q1[2], q1[3], qh[j].u[3], ql[j].u[3]);
-                } else {
-                    qh[j].v = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo);
-                }
+            if (QF32) {
+                const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                const f32x4 q0 = act ? qraw[j][0] : z, q1 = act ? qraw[j][1] : z;
+                split2(q0[0], q0[1], qh[j].u[0], ql[j].u[0]);
+                split2(q0[2], q0[3], qh[j].u[1], ql[j].u[1]);
+                split2(q1[0], q1[1], qh[j].u[2], ql[j].u[2]);
+                split2(q1[2], q1[3], qh[j].u[3], ql[j].u[3]);
+            } else {
+                qh[j].v = act ? qb[j] : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
             }
         }
     }
@@ -476,8 +501,6 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t tile_any[kMaxMaskedTiles];
     __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
-    __shared__ int s_start[kMaxFields], vlen[kMaxFields];
-    __shared__ unsigned long long anc_l[kMaxFields];
     __shared__ uint16_t act_list[kMaxChunkTilesReg];
     __shared__ int n_act_sh;
     __shared__ float red_m[4][NR], red_l[4][NR];
@@ -499,8 +522,7 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     const int mt0 = max(cb0, a.P >> 5);
     const int nmt = max(0, blk_end - mt0);
 
-    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, s_start, vlen, anc_l,
-                         bmask, rowmask, tile_any);
+    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, bmask, rowmask, tile_any);
     if (wave == 0) {
         int base = 0;
         for (int c0 = 0; c0 < a.CB; c0 += 64) {               // CB <= kMaxChunkTilesReg
@@ -720,30 +742,22 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
 template <int D, int NRT, int CB>
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm) {
     constexpr int DT = D / 32, NR = NRT * 32, Q4 = NRT * DT * 4 * 64;
-    const int q4 = blockIdx.x * 256 + threadIdx.x;
+    const int q4 = blockIdx.x * blockDim.x + threadIdx.x;
     if (q4 >= Q4) return;
     const int zr = blockIdx.y, z = zr / a.n_rg, rg = zr % a.n_rg;
     const int b = z / a.Hkv, kvh = z % a.Hkv;
     const int lane = q4 & 63, i4 = (q4 >> 6) & 3, dt = (q4 >> 8) % DT, rt = (q4 >> 8) / DT;
     const int r = rt * 32 + (lane & 31);
     const int d0 = 32 * dt + 8 * i4 + 4 * (lane >> 5);
-    const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
-    if (ri.m < 0) {
-        // rows of inactive branches: zero in the fp32 output, nothing for fragments
-        const int gr = rg * NR + r, jr = gr / a.G, ridx = jr / sm.T;
-        if (a.out_f32 && ridx < sm.R) {
-            const int m = (b * sm.R + ridx) * sm.T + jr % sm.T;
-            const int head = kvh * a.G + gr % a.G;
-            *reinterpret_cast<f32x4*>(a.out_f32 + ((size_t)m * a.Hq + head) * D + d0) =
-                f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-        return;
-    }
+    // The partials are requested before the branch tables are looked at (their
+    // addresses do not depend on them); rows of inactive branches read theirs
+    // for nothing.
     const size_t p0 = (size_t)zr * a.n_chunks;
     const f32x4* __restrict__ po = reinterpret_cast<const f32x4*>(a.part_o) + p0 * Q4 + q4;
     const float2* __restrict__ pml = reinterpret_cast<const float2*>(a.part_ml) + p0 * NR + r;
     float mg = kNegBig, L = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    RowInfo ri{-1, 0, -1, 0};
     for (int c0 = 0; c0 < a.n_chunks; c0 += CB) {
         float2 ml[CB];
         f32x4 o[CB];
@@ -753,6 +767,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm
             ml[j] = pml[(size_t)c * NR];
             o[j] = po[(size_t)c * Q4];
         }
+        if (c0 == 0) ri = row_info(rg * NR + r, b, kvh, a.G, sm);
         // all loads above are in flight together; entries past the last chunk
         // (repeats of it) get weight 0 instead of a branch, which would push the
         // arrays out of registers and serialise the loads
@@ -765,6 +780,17 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm
             acc = acc * e_old + o[j] * e_new;
             mg = mn;
         }
+    }
+    if (ri.m < 0) {
+        // rows of inactive branches: zero in the fp32 output, nothing for fragments
+        const int gr = rg * NR + r, jr = gr / a.G, ridx = jr / sm.T;
+        if (a.out_f32 && ridx < sm.R) {
+            const int m = (b * sm.R + ridx) * sm.T + jr % sm.T;
+            const int head = kvh * a.G + gr % a.G;
+            *reinterpret_cast<f32x4*>(a.out_f32 + ((size_t)m * a.Hq + head) * D + d0) =
+                f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        return;
     }
     acc *= L > 0.f ? 1.0f / L : 0.f;
     if (a.out_f32) {
@@ -791,12 +817,23 @@ void launch_t(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
         else hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), grid, block, 0, st, a, sm);
     }
     constexpr int Q4 = NRT * (D / 32) * 4 * 64;
-    const dim3 mgrid((Q4 + 255) / 256, z * a.n_rg);
-    if (a.n_chunks <= 4) hipLaunchKernelGGL((attn_merge_kernel<D, NRT, 4>), mgrid, dim3(256), 0, st, a, sm);
-    else hipLaunchKernelGGL((attn_merge_kernel<D, NRT, 16>), mgrid, dim3(256), 0, st, a, sm);
+    // one wavefront per workgroup: the partials of a row group come in through as
+    // many compute units as possible (each takes in only so many bytes per clock)
+    constexpr int mb = 64;
+    const dim3 mgrid((Q4 + mb - 1) / mb, z * a.n_rg);
+    if (a.n_chunks <= 4) hipLaunchKernelGGL((attn_merge_kernel<D, NRT, 4>), mgrid, dim3(mb), 0, st, a, sm);
+    else hipLaunchKernelGGL((attn_merge_kernel<D, NRT, 16>), mgrid, dim3(mb), 0, st, a, sm);
 }
 
 }  // namespace
+
+void launch_mask_words(const StepMeta& sm, const uint64_t* anc, int P, int n_tiles, uint32_t* words,
+                       hipStream_t st) {
+    const long n = (long)sm.B * n_tiles * sm.R * sm.T;
+    if (n <= 0) return;
+    hipLaunchKernelGGL(mask_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, sm, anc, P, n_tiles,
+                       words);
+}
 
 void launch_attention(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
     if (a.D == 128) {

@@ -50,7 +50,7 @@ struct fdc_ctx {
     char* ws = nullptr;
     size_t ws_bytes = 0;
     struct Off {
-        size_t anc, slot_start, slot_tab, inv_freq, rope_tab, meta, x, a_hi, a_lo, o_hi, o_lo, h_hi, h_lo, q,
+        size_t anc, slot_start, mask_words, inv_freq, rope_tab, meta, x, a_hi, a_lo, o_hi, o_lo, h_hi, h_lo, q,
             part, logits, attn_o, attn_ml, tok_tmp, end;
     } off{};
     size_t meta_ints = 0;
@@ -60,6 +60,9 @@ struct fdc_ctx {
     hipEvent_t stage_ev[kStageSlots] = {};
     bool stage_used[kStageSlots] = {};
     int stage_next = 0;
+    std::vector<int32_t> meta_last;      // the tables the device holds (branch_field, branch_off, valid_len)
+    int meta_last_T = 0;                 // ... their T (0: none valid) and the stream they were enqueued on
+    hipStream_t meta_last_stream = nullptr;
     int32_t* drv_host = nullptr;         // pinned: token inputs [Mmax], token outputs [Mmax] of the CoT driver
 
     // optional per-kernel timing with HIP events (benchmarks only)
@@ -116,7 +119,7 @@ void plan_attention(fdc_ctx* c) {
     const double layer_kv_bytes = 4.0 * c->B * c->m.n_kv_heads * (double)c->Npad * c->m.head_dim;
     const bool large = layer_kv_bytes >= 64e6;
     c->attn_variant = large ? 1 : 0;
-    long want_wgs = (large ? 256L : 64L) * (c->m.head_dim == 128 ? 1 : 2);
+    long want_wgs = (large ? 256L : 128L) * (c->m.head_dim == 128 ? 1 : 2);
     if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
     if (const char* e = std::getenv("FDC_ATTN_VARIANT")) c->attn_variant = std::atoi(e) == 1 ? 1 : 0;
     const long t0 = c->P / 32, masked_total = c->NB - t0;
@@ -163,7 +166,7 @@ size_t carve(fdc_ctx* c) {
     const size_t Nqkv = (size_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim;
     c->off.anc = take(sizeof(uint64_t) * c->F);
     c->off.slot_start = take(sizeof(int32_t) * c->F);
-    c->off.slot_tab = take(sizeof(uint32_t) * std::max(1, c->Npad - c->P));
+    c->off.mask_words = take(sizeof(uint32_t) * (size_t)c->Mmax * std::max(1, c->NB - c->P / 32));
     c->off.inv_freq = take(sizeof(double) * (m.head_dim / 2));
     c->off.rope_tab = take(sizeof(float2) * (size_t)c->Npad * (m.head_dim / 2));
     c->meta_ints = (size_t)2 * c->B * c->Rmax + (size_t)c->B * c->F;
@@ -216,22 +219,15 @@ int32_t check_step(const fdc_ctx* c, int R, int T, const int32_t* bf, const int3
     return FDC_OK;
 }
 
-// copies branch tables + valid_len to the device through the pinned ring
+// Copies branch tables + valid_len to the device through the pinned ring and
+// builds the step's visibility words from them.  A call with the tables the
+// device already holds (the attention of another layer in the same state, on the
+// same stream) reuses both.
 int32_t upload_meta(fdc_ctx* c, int R, const int32_t* bf, const int32_t* bo, hipStream_t st,
                     StepMeta* sm, int T) {
-    const int slot = c->stage_next;
-    c->stage_next = (slot + 1) % kStageSlots;
-    if (c->stage_used[slot]) FDC_HIP(hipEventSynchronize(c->stage_ev[slot]));
-    int32_t* h = c->stage[slot];
     const size_t nbr = (size_t)c->B * R;
-    std::memcpy(h, bf, sizeof(int32_t) * nbr);
-    std::memcpy(h + nbr, bo, sizeof(int32_t) * nbr);
-    std::memcpy(h + 2 * nbr, c->valid_len.data(), sizeof(int32_t) * c->B * c->F);
-    int32_t* d = c->at<int32_t>(c->off.meta);
     const size_t n = 2 * nbr + (size_t)c->B * c->F;
-    FDC_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * n, hipMemcpyHostToDevice, st));
-    FDC_HIP(hipEventRecord(c->stage_ev[slot], st));
-    c->stage_used[slot] = true;
+    int32_t* d = c->at<int32_t>(c->off.meta);
     sm->branch_field = d;
     sm->branch_off = d + nbr;
     sm->valid_len = d + 2 * nbr;
@@ -240,6 +236,28 @@ int32_t upload_meta(fdc_ctx* c, int R, const int32_t* bf, const int32_t* bo, hip
     sm->R = R;
     sm->T = T;
     sm->F = c->F;
+    std::vector<int32_t>& last = c->meta_last;
+    if (c->meta_last_T == T && c->meta_last_stream == st && last.size() == n &&
+        std::equal(bf, bf + nbr, last.begin()) && std::equal(bo, bo + nbr, last.begin() + nbr) &&
+        std::equal(c->valid_len.begin(), c->valid_len.end(), last.begin() + 2 * nbr))
+        return FDC_OK;
+    c->meta_last_T = 0;                                  // nothing valid until all of it is enqueued
+    const int slot = c->stage_next;
+    c->stage_next = (slot + 1) % kStageSlots;
+    if (c->stage_used[slot]) FDC_HIP(hipEventSynchronize(c->stage_ev[slot]));
+    int32_t* h = c->stage[slot];
+    std::memcpy(h, bf, sizeof(int32_t) * nbr);
+    std::memcpy(h + nbr, bo, sizeof(int32_t) * nbr);
+    std::memcpy(h + 2 * nbr, c->valid_len.data(), sizeof(int32_t) * c->B * c->F);
+    FDC_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * n, hipMemcpyHostToDevice, st));
+    FDC_HIP(hipEventRecord(c->stage_ev[slot], st));
+    c->stage_used[slot] = true;
+    launch_mask_words(*sm, c->at<uint64_t>(c->off.anc), c->P, c->NB - c->P / 32,
+                      c->at<uint32_t>(c->off.mask_words), st);
+    FDC_HIP(hipGetLastError());
+    last.assign(h, h + n);
+    c->meta_last_T = T;
+    c->meta_last_stream = st;
     return FDC_OK;
 }
 
@@ -252,8 +270,8 @@ void fill_attn(const fdc_ctx* c, int layer, int R, int T, AttnArgs* a) {
     a->vc = c->vc + (size_t)layer * c->kv_layer_elems;
     a->part_o = c->at<float>(c->off.attn_o);
     a->part_ml = c->at<float>(c->off.attn_ml);
-    a->anc = c->at<uint64_t>(c->off.anc);
-    a->slot_tab = c->at<uint32_t>(c->off.slot_tab);
+    a->mask_words = c->at<uint32_t>(c->off.mask_words);
+    a->mw_tiles = c->NB - c->P / 32;
     a->Hq = m.n_q_heads;
     a->Hkv = m.n_kv_heads;
     a->G = G;
@@ -500,19 +518,15 @@ int32_t fdc_set_workspace(fdc_ctx* c, void* ws, size_t bytes, void* stream) {
     if (bytes < c->off.end) return fail(FDC_EINVAL, "workspace of %zu bytes, %zu needed", bytes, c->off.end);
     hipStream_t st = (hipStream_t)stream;
     c->ws = (char*)ws;
+    c->meta_last_T = 0;
     c->ws_bytes = bytes;
     // template tables (pageable host memory: the copies complete before return)
-    std::vector<uint32_t> tab(std::max(1, c->Npad - c->P), 0xffffffffu);
-    for (int f = 0; f < c->F; ++f)
-        for (int t = 0; t < c->slot_len[f]; ++t)
-            tab[c->slot_start[f] - c->P + t] = (uint32_t)f | ((uint32_t)t << 8);
     std::vector<double> inv(c->m.head_dim / 2);
     for (int i = 0; i < c->m.head_dim / 2; ++i)
         inv[i] = std::pow((double)c->m.rope_base, -2.0 * i / c->m.head_dim);
     FDC_HIP(hipMemsetAsync(ws, 0, c->off.end, st));
     FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.anc), c->anc.data(), sizeof(uint64_t) * c->F, hipMemcpyHostToDevice, st));
     FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.slot_start), c->slot_start.data(), sizeof(int32_t) * c->F, hipMemcpyHostToDevice, st));
-    FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.slot_tab), tab.data(), sizeof(uint32_t) * tab.size(), hipMemcpyHostToDevice, st));
     FDC_HIP(hipMemcpyAsync(c->at<void>(c->off.inv_freq), inv.data(), sizeof(double) * inv.size(), hipMemcpyHostToDevice, st));
     launch_rope_table(c->at<double>(c->off.inv_freq), c->at<float2>(c->off.rope_tab), c->Npad, c->m.head_dim / 2, st);
     FDC_HIP(hipGetLastError());

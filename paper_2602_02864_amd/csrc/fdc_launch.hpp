@@ -87,8 +87,8 @@ struct AttnArgs {
     const uint16_t* vc;
     float* part_o;            // [z*n_rg][n_chunks][NR*D]
     float* part_ml;           // [z*n_rg][n_chunks][NR][2]
-    const uint64_t* anc;      // [F]
-    const uint32_t* slot_tab; // [Npad - P]: field | offset << 8, ~0 for tile padding
+    const uint32_t* mask_words; // the step's visibility words [B][mw_tiles][R*T] (launch_mask_words)
+    int mw_tiles;             // tiles that reach past the prefix: NB - P / 32
     float* out_f32;           // merge output: fp32 [M][Hq*D] ...
     uint16_t* out_hi;         // ... or fragments with K = Hq*D
     uint16_t* out_lo;
@@ -98,5 +98,8 @@ struct AttnArgs {
     float scale_log2;         // log2(e) / sqrt(D)
 };
 void launch_attention(const AttnArgs& a, const StepMeta& sm, hipStream_t st);
+// once per step, after the step's tables are on the device and before its first attention
+void launch_mask_words(const StepMeta& sm, const uint64_t* anc, int P, int n_tiles, uint32_t* words,
+                       hipStream_t st);
 
 }  // namespace fdc
