@@ -159,6 +159,26 @@ def test_masked_attention_matches_oracle(name, seed, F, P, max_slot, p, B, T):
     assert err < 2e-3, err
 
 
+@pytest.mark.parametrize("name,seed,F,P,max_slot,p,B,T", [
+    ("g1d64", 1, 7, 37, 9, 0.3, 2, 1),
+    ("g7d64", 3, 5, 0, 20, 0.6, 2, 2),
+    ("g7d128", 4, 12, 300, 64, 0.3, 1, 1),
+    ("g4d128", 6, 6, 100, 16, 1.0, 2, 4),
+    ("g7d128", 7, 3, 31, 5, 0.0, 1, 3),
+    ("g4d128", 8, 40, 64, 6, 0.1, 1, 1),
+])
+def test_masked_attention_register_variant_on_small_ragged_shapes(monkeypatch, name, seed, F, P, max_slot, p, B, T):
+    """The library picks the kernel that keeps K/V tiles in registers only for
+    large caches (workloads 3 and 4); here it is forced onto the small ragged
+    cases (the context reads FDC_ATTN_VARIANT when it is created), so that both
+    kernels see ragged prefixes, inactive rows, T > 1 and unwritten positions."""
+    monkeypatch.setenv("FDC_ATTN_VARIANT", "1")
+    dims = ATT_DIMS[name]
+    tpl = random_dag_template(500 + seed, F, P, max_slot, p, dims.vocab)
+    err = _attention_case(dims, tpl, B, T, seed)
+    assert err < 2e-3, err
+
+
 def test_masked_attention_microbenchmark_shape_sampled():
     """Workload 3 geometry (16 fields x 64 slots, prefix 4096, 32/8 heads, D 128)
     at 2 scenes: every branch active at offset 32, all other slots full."""
