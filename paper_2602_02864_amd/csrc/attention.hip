@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void mask_words_kernel(StepMeta sm, const uint
 // copied to the rows.  Ends with a barrier.
 template <int NR, int NT>
 __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& sm, int b, int kvh, int rg, int mt0,
-                                             int nmt, int* row_m, int* row_head, int* row_field, int* row_off,
+                                             int nmt, int* row_m, int* row_head,
                                              uint32_t (*bmask)[NR], uint32_t (*rowmask)[NR], uint32_t* tile_any) {
     const int tid = threadIdx.x;
     // branch-token rows of this row group: jr = (rg * NR + r) / G
@@ -197,8 +197,6 @@ __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& 
         const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
         row_m[r] = ri.m;
         row_head[r] = ri.head;
-        row_field[r] = ri.field;
-        row_off[r] = ri.off;
     }
     for (int t = tid; t < nmt; t += NT) tile_any[t] = 0u;
     __syncthreads();
@@ -223,7 +221,7 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     __shared__ uint32_t bmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t tile_any[kMaxMaskedTiles];
-    __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
+    __shared__ int row_m[NR], row_head[NR];
     __shared__ uint16_t act_list[kStreams][kMaxChunkTiles / kStreams];
     __shared__ int n_act[kStreams];
     __shared__ float xm[NR], xl[NR];
@@ -233,7 +231,6 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int strm = wave / NRT, rt = wave % NRT;
     const int r32 = lane & 31, hh = lane >> 5;
-    const int F = sm.F;
     const int cb0 = chunk_start(a, chunk), blk_end = min(a.NB, chunk_start(a, chunk + 1));
     const int mt0 = max(cb0, a.P >> 5);             // first tile of the chunk that reaches past the prefix
     const int nmt = max(0, blk_end - mt0);
@@ -266,7 +263,7 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
     }
 
     // ---- start-up: rows, visibility words, tile lists ---
-    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, bmask, rowmask, tile_any);
+    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, bmask, rowmask, tile_any);
     if (wave < kStreams) {
         // candidates of stream w: tiles cb0 + w, cb0 + w + 2, ...; keep the visible ones
         const int blk = cb0 + wave + kStreams * lane;
@@ -500,7 +497,7 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     __shared__ uint32_t bmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
     __shared__ uint32_t tile_any[kMaxMaskedTiles];
-    __shared__ int row_field[NR], row_off[NR], row_m[NR], row_head[NR];
+    __shared__ int row_m[NR], row_head[NR];
     __shared__ uint16_t act_list[kMaxChunkTilesReg];
     __shared__ int n_act_sh;
     __shared__ float red_m[4][NR], red_l[4][NR];
@@ -517,12 +514,11 @@ __global__ __launch_bounds__(256) void attn_partial_reg_kernel(AttnArgs a, StepM
     const int b = z / a.Hkv, kvh = z % a.Hkv;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int r32 = lane & 31, hh = lane >> 5;
-    const int F = sm.F;
     const int cb0 = chunk_start(a, chunk), blk_end = min(a.NB, chunk_start(a, chunk + 1));
     const int mt0 = max(cb0, a.P >> 5);
     const int nmt = max(0, blk_end - mt0);
 
-    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, row_field, row_off, bmask, rowmask, tile_any);
+    build_tables<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, bmask, rowmask, tile_any);
     if (wave == 0) {
         int base = 0;
         for (int c0 = 0; c0 < a.CB; c0 += 64) {               // CB <= kMaxChunkTilesReg
