@@ -420,8 +420,12 @@ def run_attention(args, rho=None, quick=False):
     alg_bytes = kv_bytes + qo_bytes
     visible_pairs = sum(bin(int(a)).count("1") for a in anc) + F
     K = 20 if quick else max(20, args.steps if args.steps > 0 else 100)
-    W = 3 if quick else max(3, args.warmup)
-    outs = [ctx.masked_attention(i % n_buf, q, bf, bo) for i in range(W)]
+    # A launch is tens of microseconds, and the device needs a few hundred milliseconds of
+    # sustained work before it runs at its steady rate (measured: 71 us per call after 300
+    # warm-up launches, 64.5 us after 3000 and after 15000): warm up for a quarter of a second.
+    W = 1500 if quick else max(4000, args.warmup)
+    for i in range(W):
+        ctx.masked_attention(i % n_buf, q, bf, bo)
     torch.cuda.synchronize()
     ctx.profile_enable(True)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
