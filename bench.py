@@ -419,11 +419,11 @@ def run_attention(args, rho=None, quick=False):
     qo_bytes = M * dims.n_q_heads * dims.head_dim * (2 + 4)
     alg_bytes = kv_bytes + qo_bytes
     visible_pairs = sum(bin(int(a)).count("1") for a in anc) + F
-    K = 20 if quick else max(20, args.steps if args.steps > 0 else 100)
+    K = 50 if quick else max(20, args.steps if args.steps > 0 else 100)
     # A launch is tens of microseconds, and the device needs a few hundred milliseconds of
     # sustained work before it runs at its steady rate (measured: 71 us per call after 300
     # warm-up launches, 64.5 us after 3000 and after 15000): warm up for a quarter of a second.
-    W = 1500 if quick else max(4000, args.warmup)
+    W = max(4000, args.warmup)
     for i in range(W):
         ctx.masked_attention(i % n_buf, q, bf, bo)
     torch.cuda.synchronize()
