@@ -291,6 +291,11 @@ int32_t fdc_cot_decode(fdc_ctx* ctx, const int32_t* start_token, const int32_t* 
  * own tokens; not advanced here).
  *  q    device bf16 [B*R*T][Hq][D]
  *  out  device fp32 [B*R*T][Hq*D]; rows of inactive branches are zero
+ * The branch tables go to the device and a small kernel derives the step's
+ * visibility words from them (one 32-key word per tile past the prefix and
+ * branch-token row; every layer's attention reads them).  A call that brings the
+ * tables of the previous call on the same stream (another layer in the same
+ * state) reuses both.
  */
 int32_t fdc_masked_attention(fdc_ctx* ctx, int32_t layer, const void* q,
                              int32_t n_branches, int32_t T,
