@@ -287,6 +287,22 @@ def test_workload2_full_depth_first_passes():
     pair.close()
 
 
+def test_workload1_full_depth_schedule_prefix():
+    """Workload 1 as benchmarked: all 24 layers at 0.5B-class widths, prefix 1536, the
+    8-field template; the first passes (6 independent fields) and, with shortened
+    contents, the two dependent fields."""
+    dims = model_dims(1)
+    tpl = template(1)
+    w = draw_weights(1, dims, random_gains=True)
+    pair = Pair(dims, tpl, w)
+    _random_prefix_kv(pair, 1)
+    lens = [2, 1, 2, 1, 2, 1, 1, 1]
+    worst, n = run_schedule(pair, lens, tpl.start_token, tag="cfg1 full depth")
+    assert n == 3
+    assert worst < 1e-3, worst
+    pair.close()
+
+
 def _driver_case(seed, header, D):
     dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=D, d_mlp=160, vocab=520)
     body = random_dag_template(1200 + seed, n_fields=6, prefix_len=21 + seed, max_slot=7, edge_prob=0.35,
