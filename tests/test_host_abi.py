@@ -30,6 +30,40 @@ def test_library_exports_every_declared_symbol():
     assert L.fdc_strerror(fb.FDC_ECYCLE).decode() != L.fdc_strerror(fb.FDC_EORDER).decode()
 
 
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as strict C99, and a C program
+    that knows nothing but the header builds, loads the library and gets the
+    ancestor words of a three-field chain from it."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_fdc.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include "fdc.h"
+int main(void) {
+    int32_t slot[3] = {2, 3, 4}, es[2] = {0, 1}, ed[2] = {1, 2}, start[3], level[3], total = 0;
+    uint64_t anc[3];
+    int32_t rc = fdc_build_mask(3, slot, 2, es, ed, 5, anc, start, level, &total);
+    if (rc != FDC_OK) { printf("error %s\n", fdc_last_error()); return 1; }
+    printf("%llu %llu %llu %d %d %d %d\n", (unsigned long long)anc[0], (unsigned long long)anc[1],
+           (unsigned long long)anc[2], start[0], start[1], start[2], total);
+    return fdc_version() >= 100 ? 0 : 2;
+}
+""")
+    inc = os.path.join(ROOT, "include")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)],
+                   check=True)
+    exe = tmp_path / "use_fdc"
+    libdir = os.path.dirname(fb.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lfdc",
+                    "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out == ["0", "1", "3", "5", "7", "10", "14"]        # anc: {}, {0}, {0, 1}; starts; N
+
+
 @pytest.mark.parametrize("F", [1, 2, 3, 4, 5])
 def test_build_mask_matches_oracle_on_all_small_dags(F):
     pairs = [(i, j) for j in range(F) for i in range(j)]
