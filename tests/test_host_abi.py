@@ -64,6 +64,13 @@ int main(void) {
     assert out == ["0", "1", "3", "5", "7", "10", "14"]        # anc: {}, {0}, {0, 1}; starts; N
 
 
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout == ""
+
+
 @pytest.mark.parametrize("F", [1, 2, 3, 4, 5])
 def test_build_mask_matches_oracle_on_all_small_dags(F):
     pairs = [(i, j) for j in range(F) for i in range(j)]
