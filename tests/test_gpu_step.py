@@ -386,3 +386,44 @@ def test_cot_decode_driver_error_paths():
         narrow.ctx.cot_decode(tpl.start_token, (), fixed)
     assert e.value.code == fb.FDC_ECAP
     narrow.close()
+
+
+@pytest.mark.parametrize("what,old,new", [
+    ("rotary sign", "x1 * c - x2 * s, x2 * c + x1 * s", "x1 * c + x2 * s, x2 * c - x1 * s"),
+    ("padding visible", "slot_start[g] + valid_len[g]] = True", "slot_start[g] + 99] = True"),
+    ("gate and up swapped", "h = silu(gu[:, :d.d_mlp]) * gu[:, d.d_mlp:]", "h = silu(gu[:, d.d_mlp:]) * gu[:, :d.d_mlp]"),
+    ("own token not visible", "vis[slot_start[f]: slot_start[f] + t + 1] = True",
+     "vis[slot_start[f]: slot_start[f] + t] = True"),
+])
+def test_the_parity_comparison_notices_a_wrong_oracle(monkeypatch, what, old, new):
+    """The comparison has teeth: against an oracle with one planted mistake (in a
+    copy of its source; the library is untouched) the same steps that pass above
+    must fail the 2e-3 check."""
+    import os
+    import types
+    import tests.helpers as H
+    src = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "fdc_oracle.py")).read()
+    assert old in src
+    mutant = types.ModuleType("fdc_oracle_mutant")
+    exec(compile(src.replace(old, new, 1), "fdc_oracle_mutant.py", "exec"), mutant.__dict__)
+    dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=64, d_mlp=160, vocab=520)
+    tpl = random_dag_template(931, n_fields=4, prefix_len=21, max_slot=6, edge_prob=0.6, vocab=dims.vocab)
+    tpl.slot_len = [max(3, s) for s in tpl.slot_len]
+    w = draw_weights(41, dims, random_gains=True, std=0.05)
+
+    def run(oracle_module):
+        monkeypatch.setattr(H, "O", oracle_module)
+        pair = Pair(dims, tpl, w, n_scenes=1, max_branches=tpl.n_fields)
+        pair.prefill_with_oracle(0, draw_prefix_embeddings(41, tpl.prefix_len, dims.d_model))
+        try:
+            roots = [f for f in range(tpl.n_fields) if not any(v == f for (_, v) in tpl.edges)]
+            for off in range(2):                          # two tokens in every root field
+                pair.step_both([roots], [[off] * len(roots)], [7 + off] * len(roots), tag=what)
+            rest = [f for f in range(tpl.n_fields) if f not in roots]
+            if rest:                                      # then the fields that see them
+                pair.step_both([rest], [[0] * len(rest)], [11] * len(rest), tag=what)
+        finally:
+            pair.close()
+    run(O)                                                # the oracle as it is: passes
+    with pytest.raises(AssertionError):
+        run(mutant)
