@@ -141,7 +141,19 @@ def run_decode(args, cfg_id, chain=False):
         return {"passes": K, "tokens": tokens, "ms_per_pass": round(ms_per_step, 4),
                 "tokens_per_s": round(tokens / (ms * 1e-3), 1)}
 
-    # second pass over the same steps with per-kernel events
+    # the same steps once more with an event after every pass: the spread of the pass latency
+    # (the passes differ: 8, then 3, then 1 ready fields); not part of the timed region above
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    marks[0].record()
+    for i in range(K):
+        one(i)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_pass = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(K)])
+    spread = {"p10": round(float(np.percentile(per_pass, 10)), 4), "p50": round(float(np.percentile(per_pass, 50)), 4),
+              "p90": round(float(np.percentile(per_pass, 90)), 4), "max": round(float(per_pass.max()), 4)}
+
+    # and once more with per-kernel events
     ctx.profile_enable(True)
     for i in range(K):
         one(i)
@@ -170,6 +182,7 @@ def run_decode(args, cfg_id, chain=False):
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_spread": spread,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg{cfg_id}: {dims.n_layers}-layer d={dims.d_model} "
@@ -384,7 +397,7 @@ def copy_reference(torch, n_bytes=1 << 30, reps=6):
             "GB/s": round(2 * n_bytes / (ms * 1e-3) / 1e9, 1)}
 
 
-def run_attention(args, rho=None, quick=False):
+def run_attention(args, rho=None, quick=False, dag_seed=None):
     """Workload 3: DAG-masked attention alone. B 16, 32/8 heads x 128, prefix
     4096, 16 branches x 64-token slots, one query token per branch at offset
     32, every other slot full.  K/V rotate over several layer-sized buffers
@@ -395,7 +408,8 @@ def run_attention(args, rho=None, quick=False):
     rho = args.rho if rho is None else rho
     n_buf = 4
     dims = model_dims(3, n_layers=n_buf)
-    tpl = template(3, rho=rho, dag_seed=args.dag_seed)
+    dag_seed = args.dag_seed if dag_seed is None else dag_seed
+    tpl = template(3, rho=rho, dag_seed=dag_seed)
     B, F, S, P = 16, tpl.n_fields, tpl.slot_len[0], tpl.prefix_len
     ctx = Context(dims, tpl.slot_len, tpl.edges, P, B, F, 1)
     g = torch.Generator(device="cuda")
@@ -442,7 +456,7 @@ def run_attention(args, rho=None, quick=False):
     ctx.close()
     gbs = alg_bytes / (k_ms * 1e-3) / 1e9
     return {"workload": f"cfg3: B=16, 32/8 heads x 128, prefix 4096, 16 branches x 64-token slots, "
-                        f"rho={rho}, dag_seed={args.dag_seed}",
+                        f"rho={rho}, dag_seed={dag_seed}",
             "closure_density": round(visible_pairs / (F * F), 4),
             "algorithmic_bytes": alg_bytes, "avg_us": round(k_ms * 1e3, 2), "avg_us_raw": round(k_raw * 1e3, 2),
             "ms_per_call_stream": round(ms, 4), "launches": K,
@@ -517,6 +531,7 @@ def main():
     ap.add_argument("--stress", action="store_true", help="cfg4: all 32 fields active (1024 rows per step)")
     ap.add_argument("--rho", type=float, default=0.3)
     ap.add_argument("--dag-seed", type=int, default=0)
+    ap.add_argument("--dag-seeds", type=int, default=5, help="cfg3 sweep: graphs drawn per random density")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-ar", action="store_true", help="skip the autoregressive (chain graph) baseline")
@@ -544,8 +559,13 @@ def main():
     del cal
     copy_ref = copy_reference(torch)
     if args.workload == "cfg3":
-        sweep = [run_attention(args, rho) for rho in ((args.rho,) if args.single else (0.0, 0.1, 0.3, 1.0))]
-        main_r = [r for r in sweep if f"rho={args.rho}," in r["workload"]] or [sweep[-1]]
+        # densities 0 and 1 have one graph each; the random ones are drawn --dag-seeds times
+        sweep = []
+        for rho in ((args.rho,) if args.single else (0.0, 0.1, 0.3, 1.0)):
+            seeds = [args.dag_seed] if args.single or rho in (0.0, 1.0) else \
+                [args.dag_seed + i for i in range(max(1, args.dag_seeds))]
+            sweep += [run_attention(args, rho, dag_seed=sd) for sd in seeds]
+        main_r = [r for r in sweep if f"rho={args.rho}, dag_seed={args.dag_seed}" in r["workload"]] or [sweep[-1]]
         a = main_r[0]
         res = {"metric": "masked-attention HBM GB/s", "value": a["achieved"], "unit": "GB/s", "n_gpus": 1,
                "steps": a["launches"], "warmup": max(3, args.warmup), "ms_per_step": a["avg_us"] / 1e3,
