@@ -475,7 +475,7 @@ def cpu_baseline(cfg_id, budget_s=12.0, max_passes=24):
     from synth_inputs import (draw_layer_weights, draw_normal_bf16, model_dims, template,
                               workload_seed)
     full = model_dims(cfg_id)
-    nl = min(4, full.n_layers)
+    nl = full.n_layers if full.d_model <= 1024 else min(4, full.n_layers)   # small models: full depth
     dims = model_dims(cfg_id, n_layers=nl)
     tpl = template(cfg_id)
     rng = workload_seed(cfg_id, "weights", 0)
@@ -509,12 +509,16 @@ def cpu_baseline(cfg_id, budget_s=12.0, max_passes=24):
                 break
         return spent, done, toks
     # about three quarters of the budget on the deep cut, the rest on the same passes at one layer
-    t_all, n_passes, tokens = run(nl, len(sched), 0.75 * budget_s)
-    t_one, _, _ = run(1, n_passes, float("inf"))
+    t_all, n_passes, tokens = run(nl, len(sched), (0.75 if nl < full.n_layers else 1.0) * budget_s)
+    t_one = run(1, n_passes, float("inf"))[0] if nl < full.n_layers else 0.0
     per_layer = max(t_all - t_one, 1e-9) / max(1, nl - 1) if nl > 1 else t_all
     head = max(t_one - per_layer, 0.0)
     t_full = per_layer * full.n_layers + head
     cores = len(os.sched_getaffinity(0))
+    if nl == full.n_layers:                      # nothing to scale: the passes ran at full depth
+        return {"value": round(tokens / t_all, 3), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                "sample": f"first {n_passes} passes ({tokens} tokens) of cfg{cfg_id} at full depth "
+                          f"({nl} layers), fp64 numpy: {t_all:.1f}s = {t_all / n_passes:.2f}s per pass"}
     return {"value": round(tokens / t_full, 3), "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"first {n_passes} passes ({tokens} tokens) of cfg{cfg_id} on a {nl}-layer cut, fp64 numpy: "
                       f"{t_all:.1f}s, the same passes on one layer {t_one:.1f}s ({t_all + t_one:.1f}s of oracle "
