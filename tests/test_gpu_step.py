@@ -427,3 +427,36 @@ def test_the_parity_comparison_notices_a_wrong_oracle(monkeypatch, what, old, ne
     run(O)                                                # the oracle as it is: passes
     with pytest.raises(AssertionError):
         run(mutant)
+
+
+@pytest.mark.parametrize("seed", [42, 1])
+def test_cot_decode_with_a_fast_response_branch_and_a_post_cot_branch(seed):
+    """A root branch that depends on nothing decodes alongside the CoT, and a final
+    branch that depends on every CoT field starts when all of them have ended and
+    sees their non-padding tokens: through fdc_cot_decode, two scenes with
+    different lengths, against the oracle's driver."""
+    from tests.helpers import GAP_MIN
+    dims = ModelDims(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=64, d_mlp=160, vocab=520)
+    tpl = random_dag_template(1400 + seed, n_fields=4, prefix_len=30 + seed, max_slot=6, edge_prob=0.4,
+                              vocab=dims.vocab)
+    tpl.slot_len = tpl.slot_len + [5, 4]                     # field 4: fast response, field 5: final branch
+    tpl.edges = list(tpl.edges) + [(f, 5) for f in range(4)]
+    tpl.start_token = tpl.start_token + [17, 23]
+    tpl.content_len = tpl.content_len + [5, 4]
+    w = draw_weights(60 + seed, dims, random_gains=True, std=0.05)
+    B, F = 2, 6
+    pair = Pair(dims, tpl, w, n_scenes=B, max_branches=F)
+    for b in range(B):
+        pair.prefill_with_oracle(b, draw_prefix_embeddings(60 + seed, tpl.prefix_len, dims.d_model, extra=b))
+    eos = list(range(0, dims.vocab, 3))
+    ref = O.run_cot_dynamic(pair.dec, tpl.start_token, eos)
+    assert ref["min_gap"] > 2 * GAP_MIN
+    got = pair.ctx.cot_decode(tpl.start_token, eos)
+    assert got["passes"] == ref["passes"]
+    for b in range(B):
+        for f in range(F):
+            n = len(ref["text"][b][f])
+            assert got["len"][b, f] == n and list(got["tok"][b, f, :n]) == ref["text"][b][f], (b, f)
+        first = ref["trace"][0]["branch_field"][b]
+        assert 4 in first and 5 not in first
+    pair.close()

@@ -615,3 +615,58 @@ def test_dynamic_driver_fixed_text_is_visible_like_a_longer_prefix():
     assert res["passes"] == want["passes"]
     with pytest.raises(ValueError):
         O.run_cot_dynamic(dec, start, eos, fixed={1: [3]})     # field 1 depends on the unfixed field 0
+
+
+def test_dynamic_driver_fast_response_and_post_cot_continuation():
+    """Two template shapes the paper names (Sec. 3.3 and its discussion): a branch
+    decoded alongside the CoT that depends on nothing (a fast response), and a
+    final branch after the CoT that sees every non-padding CoT token.  With a
+    chain-shaped CoT the final branch must equal ordinary causal decoding over
+    prefix + CoT tokens (padding and the fast response skipped, position ids
+    kept), and the fast response must equal decoding its field alone."""
+    P, S = 4, 4
+    slot_len = [S, S, S, 3, 3]                      # CoT fields 0-2 (a chain), 3: fast response, 4: final
+    edges = [(0, 1), (1, 2), (0, 4), (1, 4), (2, 4)]
+    start = [5, 9, 13, 21, 33]
+    eos = set(range(1, TINY.vocab, 4))
+    tpl = chain_template(3, S, P, TINY.vocab)       # only for the weight draw
+    w, _ = _tiny_setup(tpl, seed_cfg=23)
+    prefix = draw_prefix_embeddings(23, P, TINY.d_model).astype(np.float64)
+    dec = O.OracleDecoder(TINY, w, P, slot_len, edges)
+    dec.prefill_prefix(0, prefix)
+    res = O.run_cot_dynamic(dec, start, eos)
+    text = res["text"][0]
+    first = res["trace"][0]["branch_field"][0]
+    assert list(first[first >= 0]) == [0, 3]        # the fast response starts with the first CoT field
+    # the fast response alone: a decoder that only ever steps field 3
+    alone = O.OracleDecoder(TINY, w, P, slot_len, edges)
+    alone.prefill_prefix(0, prefix)
+    tok, want = start[3], []
+    for o in range(slot_len[3]):
+        tok = int(alone.step([[3]], [[o]], tok_in=[[[tok]]])["tok"][0])
+        want.append(tok)
+        if tok in eos:
+            break
+    assert text[3] == want
+    # the final branch: plain causal decoding over prefix + the CoT's written tokens + its own
+    emb = np.asarray(w["emb"], dtype=np.float64)
+    slot_start, _ = O.slot_layout(P, slot_len)
+    rows, pos = [r for r in prefix], list(range(P))
+    for f in range(3):
+        inputs = [start[f]] + text[f][:-1]
+        for o, t in enumerate(inputs):
+            rows.append(emb[t])
+            pos.append(slot_start[f] + o)
+    tok, want = start[4], []
+    for o in range(slot_len[4]):
+        rows.append(emb[tok])
+        pos.append(slot_start[4] + o)
+        logits, _ = _torch_reference_logits(TINY, w, np.array(rows), np.array(pos))
+        tok = int(np.argmax(logits[-1]))
+        want.append(tok)
+        if tok in eos:
+            break
+    assert text[4] == want
+    # it started only after the whole chain had finished
+    started = next(i for i, p in enumerate(res["trace"]) if 4 in p["branch_field"][0])
+    assert started == sum(len(text[f]) for f in range(3))
