@@ -200,13 +200,232 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
     }
 }
 
+// Eight wavefronts, two per SIMD, for the wide tiles.  How fast a compute unit
+// takes data in from L2 is set by the number of wavefronts that issue loads
+// (about 5 bytes per clock each), and four of them cannot feed the matrix pipe;
+// with two wavefronts per SIMD the 16x16x32 instruction keeps the pipe full too
+// (measured: 90-98 % of peak, against 55-62 % with one).  The workgroup still
+// owns 128 rows x (32 * NTW) features; the wavefronts form a WM x (8 / WM) grid
+// (2 x 4 as launched: 64 rows x 5 feature tiles each at NTW = 10).  Row
+// fragments (bf16 head + tail) go through the three-stage LDS ring as above, two
+// fetched per wavefront and k tile; the weight fragments go straight from memory
+// into matrix-instruction operands (the wavefronts with the same feature tiles
+// ask for the same lines at the same time and the L1 serves them), and the
+// registers of a weight fragment are refilled, right after its last use, with
+// the fragment four k tiles ahead.  A wavefront fits 256 registers.  With an odd
+// number of feature tiles per wavefront a gate tile and its up tile can end up
+// in neighbouring wavefronts: the SwiGLU epilogue passes that one tile through
+// LDS.  (A 4 x 2 grid needs no such exchange but asks the L1 for every weight
+// line four times and measured slower than the four-wavefront kernel.)
+template <int NTW, int EPI, int WM>
+__global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan p) {
+    constexpr int NFA = 2 * kWgMTiles;                 // row fragments per k tile: heads, tails
+    constexpr int WN = 8 / WM;                         // wavefronts along the features
+    constexpr int MF = kWgMTiles / WM;                 // 16-row fragments per wavefront
+    constexpr int TW = 2 * NTW / WN;                   // 16-feature tiles per wavefront
+    static_assert(2 * NTW % WN == 0, "feature tiles must divide over the wavefronts");
+    __shared__ uint4 lds[kStages][NFA][64];
+
+    // the wavefront's index as a scalar: what follows from it (tile numbers, base
+    // addresses) then lives in scalar registers, and the loads take a scalar base
+    // plus the lane's 16-byte offset
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int per_die = gridDim.x >> 3;
+    const int task = (blockIdx.x & 7) * per_die + (blockIdx.x >> 3);
+    if (task >= p.n_groups * p.m_blocks * p.S) return;
+    const int mb = task % p.m_blocks;
+    const int ng = (task / p.m_blocks) % p.n_groups;
+    const int s = task / (p.m_blocks * p.n_groups);
+    const int kt0 = s * p.kt_split;
+    const int nkt = min(p.KT, kt0 + p.kt_split) - kt0;
+
+    // the two row fragments this wavefront stages each k tile: fragment `wave`
+    // as head and as tail
+    const uint16_t* src[2];
+    {
+        const int mt = min(mb * kWgMTiles + wave, p.m_tiles - 1);
+        const size_t off = ((size_t)mt * p.KT + kt0) * 512;
+        src[0] = a.act_hi + off;
+        src[1] = a.act_lo + off;
+    }
+    // its weight fragments; past the last feature tile the last one is re-read
+    // (what it produces is never stored)
+    const int tile_first = ng * 2 * NTW + wn * TW;
+    const uint16_t* wsrc[TW];
+#pragma unroll
+    for (int t = 0; t < TW; ++t) {
+        const int tile = min(tile_first + t, p.n_tiles - 1);
+        wsrc[t] = a.w + ((size_t)tile * p.KT + kt0) * 512;
+    }
+
+    f32x4 acc[MF][TW];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+        for (int t = 0; t < TW; ++t) acc[mf][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // weight fragments of k tile t travel in register set t % NBS: four sets where a
+    // wavefront has few tiles (the refill then runs four k tiles ahead), two otherwise
+    constexpr int NBS = TW <= 5 ? 4 : 2;
+    f32x4 g0[2], g1[2];
+    f32x4 b0[TW], b1[TW], b2[NBS == 4 ? TW : 1], b3[NBS == 4 ? TW : 1];
+#define FDC_FETCH(g, i)                                                                    \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
+        g[j] = *reinterpret_cast<const f32x4*>(src[j] + (size_t)min((i), nkt - 1) * 512 + lane * 8)
+#define FDC_FETCHW1(b, t, i)                                                               \
+    b[t] = *reinterpret_cast<const f32x4*>(wsrc[t] + (size_t)min((i), nkt - 1) * 512 + lane * 8)
+#define FDC_PARK(g, stg)                                                                   \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
+        *reinterpret_cast<f32x4*>(&lds[stg][wave + 8 * j][lane]) = g[j]
+    // k tile i: rows out of ring stage i % 3, weights out of `b`.  `g` holds the
+    // rows of tile i+2 (requested two iterations ago): they go into the stage
+    // tile i-1 occupied, and the rows of tile i+4 are requested into `g`.
+    // (Reading the row operands of the next tile half way through an iteration, so
+    // that none starts with a wait for LDS, measured 4 % slower.)
+    bf16x8 ah[MF], al[MF];
+#define FDC_ROWS(dh, dl, stg_)                                                             \
+    _Pragma("unroll") for (int mf = 0; mf < MF; ++mf) {                                    \
+        dh[mf] = __builtin_bit_cast(bf16x8, lds[stg_][MF * wm + mf][lane]);                \
+        dl[mf] = __builtin_bit_cast(bf16x8, lds[stg_][8 + MF * wm + mf][lane]);            \
+    }
+#define FDC_ITER(g, b, i)                                                                  \
+    {                                                                                      \
+        const int into = stg == 0 ? 2 : stg - 1; /* (i + 2) % 3 */                         \
+        FDC_PARK(g, into);                                                                 \
+        FDC_FETCH(g, (i) + 4);                                                             \
+        FDC_ROWS(ah, al, stg);                                                             \
+        _Pragma("unroll") for (int t = 0; t < TW; ++t) {                                   \
+            const bf16x8 wv = __builtin_bit_cast(bf16x8, b[t]);                            \
+            _Pragma("unroll") for (int mf = 0; mf < MF; ++mf) {                            \
+                acc[mf][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, ah[mf], acc[mf][t], 0, 0, 0); \
+                acc[mf][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, al[mf], acc[mf][t], 0, 0, 0); \
+            }                                                                              \
+            FDC_FETCHW1(b, t, (i) + NBS);                                                  \
+        }                                                                                  \
+        lds_barrier();                                                                     \
+        stg = stg == 2 ? 0 : stg + 1;                                                      \
+    }
+    if (nkt > 0) {
+        FDC_FETCH(g0, 0);
+        FDC_FETCH(g1, 1);
+        _Pragma("unroll") for (int t = 0; t < TW; ++t) FDC_FETCHW1(b0, t, 0);
+        _Pragma("unroll") for (int t = 0; t < TW; ++t) FDC_FETCHW1(b1, t, 1);
+        if (NBS == 4) {
+            _Pragma("unroll") for (int t = 0; t < TW; ++t) FDC_FETCHW1(b2, t, 2);
+            _Pragma("unroll") for (int t = 0; t < TW; ++t) FDC_FETCHW1(b3, t, 3);
+        }
+        FDC_PARK(g0, 0);
+        FDC_FETCH(g0, 2);
+        FDC_PARK(g1, 1);
+        FDC_FETCH(g1, 3);
+        lds_barrier();
+        int stg = 0, i = 0;
+        if (NBS == 4) {
+            for (; i + 3 < nkt; i += 4) {
+                FDC_ITER(g0, b0, i);
+                FDC_ITER(g1, b1, i + 1);
+                FDC_ITER(g0, b2, i + 2);
+                FDC_ITER(g1, b3, i + 3);
+            }
+            if (i < nkt) FDC_ITER(g0, b0, i);
+            if (i + 1 < nkt) FDC_ITER(g1, b1, i + 1);
+            if (i + 2 < nkt) FDC_ITER(g0, b2, i + 2);
+        } else {
+            for (; i + 1 < nkt; i += 2) {
+                FDC_ITER(g0, b0, i);
+                FDC_ITER(g1, b1, i + 1);
+            }
+            if (i < nkt) FDC_ITER(g0, b0, i);
+        }
+    }
+#undef FDC_ITER
+#undef FDC_ROWS
+#undef FDC_FETCH
+#undef FDC_FETCHW1
+#undef FDC_PARK
+
+    // accumulator register e of lane l in block (mf, t):
+    //   y[m = 16 * (row fragment) + l % 16][n = 16 * tile + 4 * (l / 16) + e]
+    if (EPI == EPI_PARTIAL) {
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf) {
+            const int m = (mb * kWgMTiles + MF * wm + mf) * 16 + (lane & 15);
+            if (m >= a.M) continue;
+#pragma unroll
+            for (int t = 0; t < TW; ++t) {
+                const int n = (tile_first + t) * 16 + 4 * (lane >> 4);
+                if (n < a.n_valid)
+                    *reinterpret_cast<f32x4*>(a.out + ((size_t)s * a.M + m) * a.N + n) = acc[mf][t];
+            }
+        }
+    } else {
+        // Tile 2u holds the gate rows, tile 2u + 1 the up rows of 16 features.  With an
+        // odd number of tiles per wavefront the pair at the seam is split: the
+        // wavefront with the odd index hands its first tile (an up tile) to its left
+        // neighbour through LDS (the ring is free by now).
+        constexpr bool SEAM = (TW % 2) != 0;
+        f32x4 seam_up[MF];
+        if (SEAM) {
+            f32x4* xb = reinterpret_cast<f32x4*>(&lds[0][0][0]);      // [wm][wn / 2][mf][lane]
+            if (wn & 1) {
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf) xb[((wm * (WN / 2) + (wn >> 1)) * MF + mf) * 64 + lane] = acc[mf][0];
+            }
+            __syncthreads();
+            if (!(wn & 1)) {
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf) seam_up[mf] = xb[((wm * (WN / 2) + (wn >> 1)) * MF + mf) * 64 + lane];
+            }
+        }
+        auto emit = [&](int m, int tile0, const f32x4& gate, const f32x4& upv) {
+            if (tile0 + 1 >= p.n_tiles) return;
+            uint16_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) split_bf16(gate[e] / (1.0f + __expf(-gate[e])) * upv[e], hi[e], lo[e]);
+            const size_t o = act_frag_index(m, (tile0 >> 1) * 16 + 4 * (lane >> 4), a.out_KT);
+            *reinterpret_cast<uint2*>(a.out_hi + o) =
+                make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
+            *reinterpret_cast<uint2*>(a.out_lo + o) =
+                make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+        };
+        // pairs of a wavefront with an even index: (0,1), (2,3), ... and, at a seam,
+        // (TW-1, the neighbour's 0); with an odd index at a seam: (1,2), (3,4), ...
+        // (two static copies, so that the accumulators keep static indices)
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf) {
+            const int m = (mb * kWgMTiles + MF * wm + mf) * 16 + (lane & 15);
+            if (m >= a.M) continue;
+            if (!SEAM || !(wn & 1)) {
+#pragma unroll
+                for (int tg = 0; tg + 1 < TW; tg += 2) emit(m, tile_first + tg, acc[mf][tg], acc[mf][tg + 1]);
+                if (SEAM) emit(m, tile_first + TW - 1, acc[mf][TW - 1], seam_up[mf]);
+            } else {
+#pragma unroll
+                for (int tg = 1; tg + 1 < TW; tg += 2) emit(m, tile_first + tg, acc[mf][tg], acc[mf][tg + 1]);
+            }
+        }
+    }
+}
+
+// The narrow tile (ntw 4: QKV, O, down at a few hundred rows) measures faster with
+// four wavefronts and 32x32x16 instructions; the wide ones (gate/up, LM head) with
+// eight wavefronts (9-10 %).
 template <int NTW>
 void launch_ntw(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
-    dim3 grid(p.grid), block(256);
-    if (epilogue == EPI_SWIGLU)
-        hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_SWIGLU>), grid, block, 0, st, a, p);
-    else
-        hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_PARTIAL>), grid, block, 0, st, a, p);
+    const dim3 grid(p.grid);
+    if (NTW >= 8) {
+        if (epilogue == EPI_SWIGLU)
+            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_SWIGLU, 2>), grid, dim3(512), 0, st, a, p);
+        else
+            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_PARTIAL, 2>), grid, dim3(512), 0, st, a, p);
+    } else {
+        if (epilogue == EPI_SWIGLU)
+            hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_SWIGLU>), grid, dim3(256), 0, st, a, p);
+        else
+            hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_PARTIAL>), grid, dim3(256), 0, st, a, p);
+    }
 }
 
 }  // namespace
