@@ -96,6 +96,15 @@ def test_many_rows_per_step_use_the_tiled_projections(seed, B, T, R, Hq, Hkv, D,
     assert _random_model_steps(seed, B, T, R, dims, n_fields=F, max_slot=12, n_steps=5) >= 2
 
 
+def test_wide_mlp_at_256_rows_uses_the_eight_wavefront_projection():
+    """An MLP wide enough (2 x 8320 gate/up features at 256 rows) that the gate/up
+    projection takes the wide tile: the eight-wavefront kernel with weights
+    straight into registers and the gate/up pair that is split between two
+    wavefronts; a vocabulary that makes the LM head take it too."""
+    dims = ModelDims(n_layers=2, d_model=64, n_q_heads=2, n_kv_heads=1, head_dim=64, d_mlp=8320, vocab=17000)
+    assert _random_model_steps(9, 8, 4, 8, dims, n_fields=8, max_slot=12, n_steps=3) >= 2
+
+
 @pytest.mark.parametrize("seed,B,P,chunk,D", [(30, 1, 70, 16, 64), (31, 2, 45, 32, 128)])
 def test_prefix_prefill_through_the_step(seed, B, P, chunk, D):
     """The prefix as field 0 of a context over the same cache: stepping it with

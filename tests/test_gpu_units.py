@@ -21,7 +21,10 @@ def _torch():
                                    # more than 16 rows: the tiled kernel (ragged rows, ragged
                                    # feature tiles, split and unsplit K)
                                    (17, 48, 64), (40, 1000, 256), (129, 1152, 896), (200, 320, 2048),
-                                   (256, 3584, 4864), (64, 37888, 512), (1000, 256, 160)])
+                                   (256, 3584, 4864), (64, 37888, 512), (1000, 256, 160),
+                                   # wide tiles (the eight-wavefront kernel): ragged rows, a feature count
+                                   # that ends inside a tile and inside a workgroup, odd and even k tiles
+                                   (130, 20008, 288), (300, 33000, 96), (1000, 9000, 160), (513, 40000, 32)])
 def test_linear_matches_fp64_matmul(M, N, K):
     """y = x W^T with bf16 weights; x is carried as bf16 head + tail, so the
     result must be fp32-accurate, far inside the 2e-3 budget."""
