@@ -316,6 +316,21 @@ size_t  fdc_linear_scratch_bytes(int32_t M, int64_t n_out, int64_t k_in);
 int32_t fdc_linear(const float* x, const void* w_packed, float* y,
                    int32_t M, int64_t n_out, int64_t k_in, void* scratch, void* stream);
 
+/* fdc_linear for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical results,
+ * but the activation fragments and split-K partials live in an 8 MiB array
+ * that is part of the library's device image (every GPU the library runs on
+ * holds its own copy until the process ends); the call allocates and frees
+ * nothing.  FDC_ECAP when fdc_linear_scratch_bytes(M, n_out, k_in) exceeds
+ * 8 MiB (8388608 bytes; every M <= 16 projection of the 7B-class shapes fits,
+ * large-M products do not): use fdc_linear then.  Nothing in the array needs
+ * to start at zero, and it keeps the previous call's contents.  All calls on one
+ * GPU share the one array: calls that overlap on a GPU (two streams, two
+ * threads) race; calls enqueued on one stream are ordered and safe. */
+int32_t fdc_linear_static(const float* x, const void* w_packed, float* y,
+                          int32_t M, int64_t n_out, int64_t k_in, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Optional per-kernel timing for benchmarks (the paper times with device events,
  * Sec. 4.1).  While enabled, every kernel launch of fdc_parallel_decode_step and

@@ -28,7 +28,7 @@ EXPORTS = [
     "fdc_kv_cache_bytes", "fdc_workspace_bytes", "fdc_set_kv_cache", "fdc_set_workspace",
     "fdc_set_layer_weights", "fdc_set_head_weights", "fdc_reset", "fdc_set_valid_len",
     "fdc_get_valid_len", "fdc_kv_append", "fdc_parallel_decode_step", "fdc_masked_attention",
-    "fdc_argmax", "fdc_linear_scratch_bytes", "fdc_linear",
+    "fdc_argmax", "fdc_linear_scratch_bytes", "fdc_linear", "fdc_linear_static",
     "fdc_profile_enable", "fdc_profile_read", "fdc_profile_kind_name",
     "fdc_profile_calibrate", "fdc_stream_copy",
     "fdc_sched_create", "fdc_sched_next", "fdc_sched_destroy",
@@ -118,6 +118,8 @@ def lib() -> C.CDLL:
     L.fdc_linear_scratch_bytes.argtypes = [i32, i64, i64]
     L.fdc_linear.restype = i32
     L.fdc_linear.argtypes = [vp, vp, vp, i32, i64, i64, vp, vp]
+    L.fdc_linear_static.restype = i32
+    L.fdc_linear_static.argtypes = [vp, vp, vp, i32, i64, i64, vp]
     L.fdc_profile_enable.restype = i32
     L.fdc_profile_enable.argtypes = [vp, i32]
     L.fdc_profile_read.restype = i32
@@ -299,6 +301,19 @@ def fdc_linear(x, w_packed, n_out: int):
     y = torch.empty(M, n_out, dtype=torch.float32, device=x.device)
     _check(lib().fdc_linear(x.data_ptr(), w_packed.data_ptr(), y.data_ptr(), M, n_out, k_in,
                             scratch.data_ptr(), _stream()))
+    return y
+
+
+def fdc_linear_static(x, w_packed, n_out: int, out=None):
+    """fdc_linear without a workspace argument (the library's static scratch array).
+    `out`: an existing fp32 [M][n_out] device tensor to write into (then the call
+    allocates nothing on the Python side either)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.is_contiguous()
+    M, k_in = x.shape
+    y = out if out is not None else torch.empty(M, n_out, dtype=torch.float32, device=x.device)
+    assert y.is_cuda and y.dtype == torch.float32 and y.shape == (M, n_out) and y.is_contiguous()
+    _check(lib().fdc_linear_static(x.data_ptr(), w_packed.data_ptr(), y.data_ptr(), M, n_out, k_in, _stream()))
     return y
 
 

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1020,14 +1021,15 @@ size_t fdc_linear_scratch_bytes(int32_t M, int64_t n_out, int64_t k_in) {
     return align_up(2 * (size_t)Mp * k_in) * 2 + align_up(sizeof(float) * S * M * n_out);
 }
 
-int32_t fdc_linear(const float* x, const void* w, float* y, int32_t M, int64_t n_out, int64_t k_in,
-                   void* scratch, void* stream) {
-    if (!x || !w || !y || !scratch) return fail(FDC_EINVAL, "null pointer argument");
-    if (M < 1 || M > kMaxRowsStep) return fail(FDC_ECAP, "M = %d outside 1..%d", M, kMaxRowsStep);
-    if (n_out <= 0 || k_in <= 0 || n_out % 4 || k_in % 32) return fail(FDC_EINVAL, "n_out must be a multiple of 4, k_in of 32");
-    if (!aligned(w) || !aligned(y) || !aligned(scratch, 256)) return fail(FDC_EINVAL, "misaligned pointer");
-    hipStream_t st = (hipStream_t)stream;
-    char* s = (char*)scratch;
+}  // extern "C"
+
+namespace {
+
+// the launches of one projection; `buf` holds the activation fragments
+// (bf16 heads, then tails) and behind them the split-K partials
+int32_t linear_enqueue(const float* x, const void* w, float* y, int32_t M, int64_t n_out, int64_t k_in,
+                       void* buf, hipStream_t st) {
+    char* s = (char*)buf;
     const int Mp = (M + 15) / 16 * 16;
     const size_t fb = align_up(2 * (size_t)Mp * k_in);
     uint16_t *hi = (uint16_t*)s, *lo = (uint16_t*)(s + fb);
@@ -1057,6 +1059,68 @@ int32_t fdc_linear(const float* x, const void* w, float* y, int32_t M, int64_t n
     if (S > 1) launch_sum_partials(part, y, S, M, n_out, st);
     FDC_HIP(hipGetLastError());
     return FDC_OK;
+}
+
+int32_t check_linear(const float* x, const void* w, const float* y, int32_t M, int64_t n_out, int64_t k_in) {
+    if (!x || !w || !y) return fail(FDC_EINVAL, "null pointer argument");
+    if (M < 1 || M > kMaxRowsStep) return fail(FDC_ECAP, "M = %d outside 1..%d", M, kMaxRowsStep);
+    if (n_out <= 0 || k_in <= 0 || n_out % 4 || k_in % 32) return fail(FDC_EINVAL, "n_out must be a multiple of 4, k_in of 32");
+    if (!aligned(w) || !aligned(y)) return fail(FDC_EINVAL, "misaligned pointer");
+    return FDC_OK;
+}
+
+// ---- scratch memory that nobody allocates -----------------------------------
+// Every GPU the library runs on holds its own copy of this array, at its own
+// address, until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: what kernels, copies and fills get is the
+// address that call returns for the current device, looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch(void** out) {
+    int dev = -1;
+    FDC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(FDC_ECAP, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        FDC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned(p, 256)) return fail(FDC_EHIP, "device %d: no usable address for the static scratch array", dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FDC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t fdc_linear(const float* x, const void* w, float* y, int32_t M, int64_t n_out, int64_t k_in,
+                   void* scratch_dev, void* stream) {
+    int32_t rc = check_linear(x, w, y, M, n_out, k_in);
+    if (rc != FDC_OK) return rc;
+    if (!scratch_dev) return fail(FDC_EINVAL, "null pointer argument");
+    if (!aligned(scratch_dev, 256)) return fail(FDC_EINVAL, "misaligned pointer");
+    return linear_enqueue(x, w, y, M, n_out, k_in, scratch_dev, (hipStream_t)stream);
+}
+
+int32_t fdc_linear_static(const float* x, const void* w, float* y, int32_t M, int64_t n_out, int64_t k_in,
+                          void* stream) {
+    int32_t rc = check_linear(x, w, y, M, n_out, k_in);
+    if (rc != FDC_OK) return rc;
+    const size_t need = fdc_linear_scratch_bytes(M, n_out, k_in);
+    if (need == 0) return fail(FDC_ECAP, "shape M=%d n_out=%lld k_in=%lld not supported", M, (long long)n_out, (long long)k_in);
+    if (need > kStaticScratchBytes)
+        return fail(FDC_ECAP, "projection needs %zu bytes of scratch, the static buffer holds %zu", need,
+                    kStaticScratchBytes);
+    void* s = nullptr;
+    rc = static_scratch(&s);
+    if (rc != FDC_OK) return rc;
+    return linear_enqueue(x, w, y, M, n_out, k_in, s, (hipStream_t)stream);
 }
 
 }  // extern "C"
