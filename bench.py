@@ -1,23 +1,35 @@
 #!/usr/bin/env python3
 """Benchmark of the parallel decoding step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg3]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg3|cfg4]
 
 A step is one pass of the whole hot path (fdc_parallel_decode_step: embedding,
 norms, QKV / O / SwiGLU projections, RoPE + KV append, DAG-masked attention, LM
 head, greedy argmax) over the branches Algorithm 1 has ready.  The default
 workload is the 7B-class configuration (28 layers, d 3584, 28/4 heads x 128,
 MLP 18944, vocab 32000; prefix 3072; 12 fields in a 3-level DAG, 64-token
-slots; batch 1; greedy): the K timed steps are the first K passes of the
-template's schedule (default: the whole schedule, wrapping around if K is
-larger).  Inputs are seeded synthetic tensors already resident in HBM.
+slots; batch 1; greedy).  Inputs are seeded synthetic tensors already resident
+in HBM.
 
-Prints ONE JSON line.  `roofline` is the dominant kernel of the step (the
-gate/up projection with fused SwiGLU: weight streaming, HBM-bound) timed with
-HIP events on the launch stream in a second pass over the same steps;
-`cpu_baseline` is the fp64 oracle timed on this host's cores on a bounded
-sample.  `attention` carries the DAG-masked attention micro-benchmark
-(workload 3) with its own HBM roofline fraction.
+Prints ONE JSON line.
+  * `ms_per_step` is the mean over the K timed steps (the first K passes of the
+    template's schedule; the whole schedule when K = 0).
+  * `value` is CoT tokens per second over the WHOLE schedule (every pass of
+    Algorithm 1 from empty slots to the last field, whatever K is): the passes
+    differ in width (8, then 3, then 1 ready fields), so the first K alone would
+    overstate the rate.  The K-step figure is kept under `first_steps`.
+  * `roofline` is the dominant kernel of the step (the gate/up projection with
+    fused SwiGLU: weight streaming, HBM-bound) timed with HIP events on the
+    launch stream in a further pass over the schedule; `rooflines` carries, beside
+    it, the DAG-masked attention micro-benchmark over mask densities (workload 3,
+    HBM) and the gate/up projection as a tiled matrix-core product at 256 rows
+    (workload 4, MFMA; counted on the method's 2*M*N*K flops).
+  * `templates` (Sec. 4.3 of the paper): three dependency graphs over the same
+    fields and token budget, each decoded in parallel, against autoregressive
+    decoding of the same tokens (a chain-shaped graph): time against
+    critical-path length, speed-up against average parallel degree.
+  * `cpu_baseline` is the fp64 oracle timed on this host's cores on a bounded
+    sample.
 """
 from __future__ import annotations
 
@@ -66,97 +78,128 @@ def weight_bytes(dims):
     return {k: 2 * v for k, v in per.items()}
 
 
-def run_decode(args, cfg_id, chain=False):
-    """Greedy template decoding of workload `cfg_id`.  chain=True replaces the
-    template's graph by a chain (field i depends on field i-1): ordinary
-    autoregressive decoding of the same fields, slots and token budget, one
-    token per pass - the baseline the paper compares against (Sec. 4.1)."""
+class Decoder:
+    """One context + its schedule (lengths known beforehand) with the greedy
+    feedback kept on the device: last_tok[f] feeds field f's next row."""
+
+    def __init__(self, torch, dims, tpl, edges, weights_of=None, seed=0):
+        from paper_2602_02864_amd import Context, fdc_schedule, lib
+        self.torch, self.tpl, self.dims = torch, tpl, dims
+        F = tpl.n_fields
+        passes = fdc_schedule(F, edges, tpl.content_len)
+        self.R = R = max(int((bf >= 0).sum()) for bf, _ in passes)
+        self.passes = [(bf[:R].copy(), bo[:R].copy()) for bf, bo in passes]
+        if weights_of is None:
+            self.ctx = Context(dims, tpl.slot_len, edges, tpl.prefix_len, 1, R, 1)
+            t0 = time.time()
+            build_model(self.ctx, dims, seed, torch)
+            log(f"[bench] model built in {time.time() - t0:.1f}s, "
+                f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
+            # prefix K/V: N(0,1) stand-ins for the prefilled vision/prompt tokens
+            g = torch.Generator(device="cuda")
+            g.manual_seed(99)
+            self.ctx.k_cache.normal_(generator=g)
+            self.ctx.v_cache.normal_(generator=g)
+        else:
+            self.ctx = Context(dims, tpl.slot_len, edges, tpl.prefix_len, 1, R, 1, share=weights_of.ctx)
+        dev = "cuda"
+        self.start = torch.tensor(tpl.start_token, dtype=torch.int32, device=dev)
+        self.idx = [torch.tensor(np.where(bf >= 0, bf, 0), dtype=torch.int64, device=dev) for bf, _ in self.passes]
+        self.sel = [torch.tensor(np.nonzero(bf >= 0)[0], dtype=torch.int64, device=dev) for bf, _ in self.passes]
+        self.fld = [torch.tensor(bf[bf >= 0], dtype=torch.int64, device=dev) for bf, _ in self.passes]
+        self.tok_out = torch.empty(R, dtype=torch.int32, device=dev)
+        self.last = self.start.clone()
+        self.L = lib()
+        self.n_tokens = sum(int((bf >= 0).sum()) for bf, _ in self.passes)
+
+    def one(self, i):
+        from paper_2602_02864_amd.binding import _p, _check, _stream
+        p = i % len(self.passes)
+        if p == 0:
+            self.ctx.reset()
+            self.last = self.start.clone()
+        bf, bo = self.passes[p]
+        tok_in = self.last[self.idx[p]].contiguous()
+        _check(self.L.fdc_parallel_decode_step(self.ctx._h, self.R, 1, _p(bf), _p(bo), tok_in.data_ptr(), None,
+                                               self.tok_out.data_ptr(), None, None, None, _stream()))
+        self.last.index_copy_(0, self.fld[p], self.tok_out.index_select(0, self.sel[p]))
+        return int((bf >= 0).sum())
+
+    def timed(self, n_steps, first=0):
+        """(milliseconds, tokens, host seconds) of steps first .. first + n_steps - 1."""
+        torch = self.torch
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        tokens = 0
+        t_wall = time.perf_counter()
+        e0.record()
+        for i in range(first, first + n_steps):
+            tokens += self.one(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1), tokens, time.perf_counter() - t_wall
+
+    def whole_schedule(self):
+        ms, tokens, _ = self.timed(len(self.passes))
+        return {"passes": len(self.passes), "tokens": tokens, "ms": round(ms, 3),
+                "ms_per_pass": round(ms / len(self.passes), 4), "tokens_per_s": round(tokens / (ms * 1e-3), 1)}
+
+
+def graph_variants(tpl):
+    """Three dependency graphs over the fields of workload 2 (same slots, same
+    content lengths, same token budget): the workload's own three levels, a flat
+    one (every field but the last independent) and a deep one (four levels)."""
+    F = tpl.n_fields
+    own = list(tpl.edges)
+    flat = [(p, F - 1) for p in range(F - 1)]
+    cut = [0, F // 3, 2 * F // 3, F - 1, F]                    # levels 0..3
+    deep = [(u, v) for lv in range(1, 4) for v in range(cut[lv], cut[lv + 1]) for u in range(cut[lv - 1], cut[lv])]
+    return [("as given: 8 roots, 3 middle fields, 1 final", own),
+            (f"flat: {F - 1} independent fields, 1 final", flat),
+            (f"deep: four levels of {cut[1]}, {cut[2] - cut[1]}, {cut[3] - cut[2]}, 1 fields", deep)]
+
+
+def run_decode(args, cfg_id):
+    """Greedy template decoding of workload `cfg_id`."""
     import torch
-    from paper_2602_02864_amd import Context, fdc_schedule
     from synth_inputs import model_dims, template
     dims = model_dims(cfg_id)
     tpl = template(cfg_id)
     F = tpl.n_fields
-    if chain:
-        tpl.edges = [(i, i + 1) for i in range(F - 1)]
-    passes = fdc_schedule(F, tpl.edges, tpl.content_len)
-    R = max(int((bf >= 0).sum()) for bf, _ in passes)
-    passes = [(bf[:R].copy(), bo[:R].copy()) for bf, bo in passes]
-    ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, 1, R, 1)
-    t0 = time.time()
-    build_model(ctx, dims, 2864000 + cfg_id, torch)
-    log(f"[bench] model built in {time.time() - t0:.1f}s, "
-        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
-    # prefix K/V: N(0,1) stand-ins for the prefilled vision/prompt tokens
-    g = torch.Generator(device="cuda")
-    g.manual_seed(99)
-    ctx.k_cache.normal_(generator=g)
-    ctx.v_cache.normal_(generator=g)
-
+    dec = Decoder(torch, dims, tpl, tpl.edges, seed=2864000 + cfg_id)
+    ctx, passes, R = dec.ctx, dec.passes, dec.R
     K = args.steps if args.steps > 0 else len(passes)
     W = args.warmup
-    if chain:
-        K = len(passes)
-    dev = "cuda"
-    # greedy feedback stays on the device: last_tok[f] feeds field f's next row
-    start = torch.tensor(tpl.start_token, dtype=torch.int32, device=dev)
-    idx = [torch.tensor(np.where(bf >= 0, bf, 0), dtype=torch.int64, device=dev) for bf, _ in passes]
-    sel = [torch.tensor(np.nonzero(bf >= 0)[0], dtype=torch.int64, device=dev) for bf, _ in passes]
-    fld = [torch.tensor(bf[bf >= 0], dtype=torch.int64, device=dev) for bf, _ in passes]
-    tok_out = torch.empty(R, dtype=torch.int32, device=dev)
-    from paper_2602_02864_amd import lib
-    from paper_2602_02864_amd.binding import _p, _check, _stream
-    L = lib()
-    state = {"last": start.clone()}
-
-    def one(i):
-        p = i % len(passes)
-        if p == 0:
-            ctx.reset()
-            state["last"] = start.clone()
-        bf, bo = passes[p]
-        tok_in = state["last"][idx[p]].contiguous()
-        _check(L.fdc_parallel_decode_step(ctx._h, R, 1, _p(bf), _p(bo), tok_in.data_ptr(), None,
-                                          tok_out.data_ptr(), None, None, None, _stream()))
-        state["last"].index_copy_(0, fld[p], tok_out.index_select(0, sel[p]))
-        return int((bf >= 0).sum())
-
     # warm-up: the paper discards the first 10 iterations
     for i in range(W):
-        one(i)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    tokens = 0
-    t_wall = time.perf_counter()
-    e0.record()
-    for i in range(K):
-        tokens += one(i)
-    e1.record()
-    torch.cuda.synchronize()
-    t_wall = time.perf_counter() - t_wall
-    ms = e0.elapsed_time(e1)
+        dec.one(i)
+    ms, tokens, t_wall = dec.timed(K)              # the K timed steps: passes 0 .. K-1 of the schedule
     ms_per_step = ms / K
-    if chain:
-        ctx.close()
-        return {"passes": K, "tokens": tokens, "ms_per_pass": round(ms_per_step, 4),
-                "tokens_per_s": round(tokens / (ms * 1e-3), 1)}
+    sched = dec.whole_schedule() if K != len(passes) else \
+        {"passes": K, "tokens": tokens, "ms": round(ms, 3), "ms_per_pass": round(ms / K, 4),
+         "tokens_per_s": round(tokens / (ms * 1e-3), 1)}
 
-    # the same steps once more with an event after every pass: the spread of the pass latency
-    # (the passes differ: 8, then 3, then 1 ready fields); not part of the timed region above
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    # the schedule once more with an event after every pass: the spread of the pass latency
+    # (the passes differ: 8, then 3, then 1 ready fields); not part of the timed regions above
+    n_all = len(passes)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_all + 1)]
     marks[0].record()
-    for i in range(K):
-        one(i)
+    for i in range(n_all):
+        dec.one(i)
         marks[i + 1].record()
     torch.cuda.synchronize()
-    per_pass = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(K)])
+    per_pass = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_all)])
+    width = np.array([int((bf >= 0).sum()) for bf, _ in passes])
     spread = {"p10": round(float(np.percentile(per_pass, 10)), 4), "p50": round(float(np.percentile(per_pass, 50)), 4),
-              "p90": round(float(np.percentile(per_pass, 90)), 4), "max": round(float(per_pass.max()), 4)}
+              "p90": round(float(np.percentile(per_pass, 90)), 4), "max": round(float(per_pass.max()), 4),
+              "by_ready_fields": {str(int(r)): {"passes": int((width == r).sum()),
+                                                "ms": round(float(per_pass[width == r].mean()), 4)}
+                                  for r in sorted(set(width.tolist()), reverse=True)}}
 
     # and once more with per-kernel events
     ctx.profile_enable(True)
-    for i in range(K):
-        one(i)
+    for i in range(n_all):
+        dec.one(i)
     torch.cuda.synchronize()
     prof = ctx.profile_read()
     ctx.profile_enable(False)
@@ -168,7 +211,7 @@ def run_decode(args, cfg_id, chain=False):
             continue
         avg = max(kms / n - ov_ms, 1e-6)           # the event pair's own cost taken off
         ent = {"avg_us": round(1e3 * avg, 2), "avg_us_raw": round(1e3 * kms / n, 2), "launches": n,
-               "share": round(avg * n / ms, 4)}
+               "share": round(avg * n / sched["ms"], 4)}
         if name in wb:
             ent["GB/s"] = round(wb[name] / (avg * 1e-3) / 1e9, 1)
         kernels[name] = ent
@@ -176,12 +219,19 @@ def run_decode(args, cfg_id, chain=False):
     dom_ms = max(prof[dom][0] / max(1, prof[dom][1]) - ov_ms, 1e-6)
     achieved = wb[dom] / (dom_ms * 1e-3) / 1e9
     total_w = sum(v * (dims.n_layers if k != "lm_head" else 1) for k, v in wb.items())
+    traffic, traffic_src = measured_traffic(f"cfg{cfg_id}", dom)
     res = {
         "metric": "CoT tokens/s in parallel decoding (greedy, batch 1)",
-        "value": round(tokens / (ms * 1e-3), 1),
+        "value": sched["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4),
+        "value_basis": f"whole schedule of Algorithm 1: {sched['tokens']} tokens in {sched['passes']} passes, "
+                       f"{sched['ms']} ms; ms_per_step is the mean of the {K} timed steps (passes 0..{K - 1})",
+        "schedule": sched,
+        "first_steps": {"steps": K, "tokens": tokens, "tokens_per_step": round(tokens / K, 3),
+                        "tokens_per_s": round(tokens / (ms * 1e-3), 1),
+                        "note": "the first passes have every root field ready; not the whole-job rate"},
         "ms_per_step_spread": spread,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -190,17 +240,19 @@ def run_decode(args, cfg_id, chain=False):
                                f"vocab={dims.vocab}; prefix {tpl.prefix_len}; {F} fields x "
                                f"{tpl.slot_len[0]}-token slots; passes {len(passes)}; "
                                f"tokens {sum(tpl.content_len)}; max ready {R}; batch 1",
-                   "tokens_per_pass": round(tokens / K, 3)},
+                   "tokens_per_pass": round(sched["tokens"] / sched["passes"], 3)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(f"cfg{cfg_id}", dom), "bytes_per_launch": wb[dom],
+                     "traffic": traffic, "traffic_source": traffic_src, "bytes_per_launch": wb[dom],
                      "avg_us": round(dom_ms * 1e3, 2)},
         "step_hbm": {"weight_bytes_per_step": total_w,
                      "floor_ms_at_peak": round(total_w / HBM_PEAK_GBS / 1e6, 4),
-                     "frac_of_floor": round(total_w / HBM_PEAK_GBS / 1e6 / ms_per_step, 4)},
+                     "frac_of_floor": round(total_w / HBM_PEAK_GBS / 1e6 / sched["ms_per_pass"], 4)},
         "kernels": kernels,
         "host_wall_ms_per_step": round(1e3 * t_wall / K, 4),
     }
+    if not args.no_ar:
+        res["templates"] = run_templates(torch, dims, tpl, dec, sched)
     if not args.no_driver and args.steps == 0:
         res["driver"] = run_driver(ctx, dims, tpl, torch)
     if args.prefill:
@@ -208,8 +260,10 @@ def run_decode(args, cfg_id, chain=False):
         # the same step, `chunk` embedding rows per pass (the paper's "CoT time" also
         # counts this input processing, Sec. 4.1; the decode figure above does not)
         chunk, P = args.prefill_chunk, tpl.prefix_len
+        g = torch.Generator(device="cuda")
+        g.manual_seed(98)
         view = ctx.prefill_view(chunk)
-        emb = torch.randn(1, P, dims.d_model, device=dev, generator=g).to(torch.bfloat16)
+        emb = torch.randn(1, P, dims.d_model, device="cuda", generator=g).to(torch.bfloat16)
         for rep in range(2):
             view.reset()
             torch.cuda.synchronize()
@@ -220,8 +274,41 @@ def run_decode(args, cfg_id, chain=False):
         res["prefill"] = {"tokens": P, "chunk": chunk, "ms": round(1e3 * dt, 2),
                           "tokens_per_s": round(P / dt, 1)}
         view.close()
-    ctx.close()
-    return res
+    return res, dec
+
+
+def run_templates(torch, dims, tpl, dec, sched_own):
+    """Sec. 4.3 of the paper as a measurement: with the token budget fixed, CoT
+    time follows the critical path (the number of passes), and the speed-up over
+    autoregressive decoding sits slightly below the average parallel degree.
+    Autoregressive decoding = the same fields, slots and tokens under a
+    chain-shaped graph (field i after field i-1): one token per pass."""
+    F = tpl.n_fields
+    chain = Decoder(torch, dims, tpl, [(i, i + 1) for i in range(F - 1)], weights_of=dec)
+    for i in range(5):
+        chain.one(i)
+    ar = chain.whole_schedule()
+    chain.ctx.close()
+    rows = []
+    for name, edges in graph_variants(tpl):
+        if edges == list(tpl.edges):
+            s = dict(sched_own)
+        else:
+            d = Decoder(torch, dims, tpl, edges, weights_of=dec)
+            for i in range(5):
+                d.one(i)
+            s = d.whole_schedule()
+            d.ctx.close()
+        degree = s["tokens"] / s["passes"]
+        speedup = ar["ms"] / s["ms"]
+        rows.append({"graph": name, "critical_path_passes": s["passes"], "tokens": s["tokens"],
+                     "average_parallel_degree": round(degree, 3), "cot_ms": s["ms"], "ms_per_pass": s["ms_per_pass"],
+                     "tokens_per_s": s["tokens_per_s"], "speedup_over_autoregressive": round(speedup, 3),
+                     "speedup_over_degree": round(speedup / degree, 3)})
+    return {"autoregressive": {**ar, "note": "chain-shaped graph over the same fields: one token per pass"},
+            "parallel": rows,
+            "note": "the paper reports 3-4x on its own templates and hardware (A100), slightly below the "
+                    "parallel degree; here the same comparison on synthetic templates, one MI355X"}
 
 
 def run_driver(ctx, dims, tpl, torch, every=40):
@@ -255,11 +342,12 @@ def run_driver(ctx, dims, tpl, torch, every=40):
 MFMA_PEAK_TFLOPS = 2500.0
 
 
-def run_multi(args):
+def run_multi(args, weights_of=None, steps=None):
     """Workload 4: the cfg2 model with 8 scenes, prefix 8192, 32 fields of 32-token
     slots in a 4-level DAG, 4 given tokens per branch per step (multi-token masked
     prefill inside each slot): 32 passes of 8 ready fields x 8 scenes x 4 tokens =
-    256 rows; with --stress one pass with all 32 fields active (1024 rows)."""
+    256 rows; with --stress one pass with all 32 fields active (1024 rows).
+    weights_of: a context that already holds the (same) model's packed weights."""
     import torch
     from paper_2602_02864_amd import Context, lib
     from paper_2602_02864_amd.binding import _p, _check, _stream
@@ -268,11 +356,14 @@ def run_multi(args):
     tpl = template(4)
     B, T, F, S = 8, 4, tpl.n_fields, tpl.slot_len[0]
     R = F if args.stress else 8
-    ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T)
-    t0 = time.time()
-    build_model(ctx, dims, 2864004, torch)
-    log(f"[bench] model built in {time.time() - t0:.1f}s, "
-        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
+    if weights_of is not None:
+        ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T, weights_from=weights_of)
+    else:
+        ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T)
+        t0 = time.time()
+        build_model(ctx, dims, 2864004, torch)
+        log(f"[bench] model built in {time.time() - t0:.1f}s, "
+            f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
     g = torch.Generator(device="cuda")
     g.manual_seed(99)
     ctx.k_cache.normal_(generator=g)
@@ -301,7 +392,7 @@ def run_multi(args):
                                           tok_out.data_ptr(), None, None, None, _stream()))
         return M
 
-    K = args.steps if args.steps > 0 else len(passes)
+    K = steps if steps else (args.steps if args.steps > 0 else len(passes))
     W = min(args.warmup, len(passes))
     for i in range(W):
         one(i)
@@ -339,6 +430,7 @@ def run_multi(args):
     dom_ms = max(prof[dom][0] / max(1, prof[dom][1]) - ov_ms, 1e-6)
     fl = 2.0 * M * wb[dom] / 2
     achieved = fl / (dom_ms * 1e-3) / 1e12
+    traffic, traffic_src = measured_traffic("cfg4", dom)
     res = {
         "metric": "CoT tokens/s in parallel decoding (given tokens, 4 per branch per step, batch 8)",
         "value": round(tokens / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -351,11 +443,9 @@ def run_multi(args):
                                f"{R} branches = {M} rows per step; passes {len(passes)}"},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": measured_traffic("cfg4", dom), "flops_per_launch": fl,
+                     "traffic": traffic, "traffic_source": traffic_src, "flops_per_launch": fl,
                      "avg_us": round(dom_ms * 1e3, 2),
-                     "note": "achieved counts 2*M*N*K; the kernel issues twice that on the matrix cores "
-                             "(activations as bf16 head + tail)",
-                     "issued_frac": round(2 * achieved / MFMA_PEAK_TFLOPS, 4)},
+                     "note": "achieved counts the method's 2*M*N*K flops"},
         "projections": {"TFLOP/s": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms else None,
                         "share_of_step": round(gemm_ms / ms, 4)},
         "kernels": kernels,
@@ -365,17 +455,22 @@ def run_multi(args):
 
 
 def measured_traffic(workload, kernel):
-    """HBM bytes per launch from the hardware counters (FETCH_SIZE + WRITE_SIZE,
-    scaled by a copy of known size), as written by rocprof_summary.py from two
-    rocprofv3 --pmc runs of this benchmark; None when no such record exists."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2602_02864_amd",
-                        "measured_traffic.json")
+    """(HBM bytes per launch, where the figure comes from).  The bytes are a STORED
+    record, not measured in this run: FETCH_SIZE + WRITE_SIZE of two earlier
+    rocprofv3 --pmc runs of this benchmark, each scaled by what the counter shows
+    for a copy of known size, written by bench_rocprof.py into
+    profiles/hbm_traffic_measured.json.  (None, reason) when no record exists."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_measured.json")
     try:
         with open(path) as f:
             rec = json.load(f).get(f"{workload}/{kernel}")
-        return rec and rec["bytes_per_launch"]
+        if not rec:
+            return None, "no stored counter record for this kernel"
+        return rec["bytes_per_launch"], ("stored rocprofv3 --pmc record (profiles/hbm_traffic_measured.json"
+                                         + (f", {rec['recorded']}" if "recorded" in rec else "")
+                                         + "), not measured in this run")
     except (OSError, ValueError, KeyError):
-        return None
+        return None, "no stored counter record"
 
 
 def copy_reference(torch, n_bytes=1 << 30, reps=6):
@@ -538,7 +633,9 @@ def main():
     ap.add_argument("--dag-seeds", type=int, default=5, help="cfg3 sweep: graphs drawn per random density")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
-    ap.add_argument("--no-ar", action="store_true", help="skip the autoregressive (chain graph) baseline")
+    ap.add_argument("--no-ar", action="store_true",
+                    help="skip the three-graph / autoregressive comparison (Sec. 4.3)")
+    ap.add_argument("--no-multi", action="store_true", help="cfg2: skip the 256-row (workload 4) leg")
     ap.add_argument("--no-driver", action="store_true", help="skip the run of the library's own Algorithm 1 loop")
     ap.add_argument("--prefill", action="store_true", help="also time the causal prefill of the prefix")
     ap.add_argument("--prefill-chunk", type=int, default=1024, help="prefix tokens per prefill pass (at most 1024)")
@@ -577,25 +674,45 @@ def main():
                "data": "synthetic", "config": {"workload": a["workload"]},
                "roofline": {"bound": "hbm", "kernel": "masked_attention", "achieved": a["achieved"],
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a["frac"],
-                            "traffic": measured_traffic("cfg3", "masked_attention")},
+                            "traffic": measured_traffic("cfg3", "masked_attention")[0],
+                            "traffic_source": measured_traffic("cfg3", "masked_attention")[1]},
                "sweep": sweep}
     elif args.workload == "cfg4":
         res = run_multi(args)
         args.no_cpu_baseline = True      # the oracle is timed on the default workload
     else:
         cfg_id = int(args.workload[3:])
-        res = run_decode(args, cfg_id)
-        if not args.no_ar and args.steps == 0:
-            # the paper's headline comparison: the same tokens decoded one per pass
-            ar = run_decode(args, cfg_id, chain=True)
-            n_pass = res["steps"]
-            ar["speedup_of_parallel_decoding"] = round(res["value"] / ar["tokens_per_s"], 3)
-            ar["average_parallel_degree"] = round(ar["passes"] / n_pass, 3)
-            ar["note"] = ("chain-shaped graph over the same fields = autoregressive decoding; the paper "
-                          "reports 3-4x on its own templates and hardware, slightly below the parallel degree")
-            res["ar_baseline"] = ar
+        res, dec = run_decode(args, cfg_id)
+        rooflines = {f"cfg{cfg_id} {res['roofline']['kernel']}": {k: res["roofline"][k] for k in
+                                                                 ("bound", "achieved", "peak", "unit", "frac")}}
+        if cfg_id == 2 and not args.no_multi:
+            # the same model at 256 rows per step (workload 4): the projections as tiled
+            # matrix-core products, a few passes
+            m = run_multi(args, weights_of=dec.ctx, steps=8)
+            res["cfg4"] = {k: m[k] for k in ("config", "ms_per_step", "value", "unit", "roofline", "projections",
+                                             "kernels")}
+            rooflines["cfg4 gate_up_swiglu (256 rows)"] = {k: m["roofline"][k] for k in
+                                                           ("bound", "achieved", "peak", "unit", "frac")}
+        dec.ctx.close()
+        del dec
         if not args.no_attention:
-            res["attention"] = run_attention(args, quick=True)
+            # DAG-masked attention alone (workload 3) over the mask densities
+            sweep = []
+            for rho in (0.0, 0.1, 0.3, 1.0):
+                seeds = [args.dag_seed] if rho in (0.0, 1.0) else \
+                    [args.dag_seed + i for i in range(max(1, min(2, args.dag_seeds)))]
+                sweep += [run_attention(args, rho, quick=True, dag_seed=sd) for sd in seeds]
+            main_a = [r for r in sweep if "rho=0.3" in r["workload"]][0]
+            res["attention"] = main_a
+            res["attention_sweep"] = [{"rho_seed": r["workload"].split("slots, ")[1],
+                                       "closure_density": r["closure_density"], "avg_us": r["avg_us"],
+                                       "achieved": r["achieved"], "frac": r["frac"]} for r in sweep]
+            fr = [r["frac"] for r in sweep]
+            rooflines["cfg3 masked_attention"] = {"bound": "hbm", "achieved": main_a["achieved"],
+                                                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": main_a["frac"],
+                                                  "frac_min_over_densities": min(fr),
+                                                  "frac_max_over_densities": max(fr)}
+        res["rooflines"] = rooflines
     if not args.no_cpu_baseline and args.workload not in ("cfg3", "cfg4"):
         t0 = time.time()
         res["cpu_baseline"] = cpu_baseline(int(args.workload[3:]))

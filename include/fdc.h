@@ -25,7 +25,8 @@
  *  - rows of a step are ordered m = (scene * R + branch) * T + t.
  *  - limits: n_fields <= 64 for a context; head_dim in {64, 128};
  *    d_model, n_q_heads*head_dim and d_mlp multiples of 32, vocab of 4;
- *    d_model <= 5120; B*R*T <= 1024 rows per step (FDC_ECAP otherwise).  Up to
+ *    d_model <= 5120; B*R*T <= 1024 rows per step; at most 65535 * 32 cache
+ *    positions per scene (FDC_ECAP otherwise).  Up to
  *    16 rows the projections stream the weights once (HBM-bound kernels), above
  *    that they run as tiled matrix-core products.
  */
@@ -98,8 +99,10 @@ int32_t fdc_build_mask(int32_t n_fields, const int32_t* slot_len,
                        uint64_t* anc_words, int32_t* slot_start, int32_t* level,
                        int32_t* total_len);
 
-/* Dense expansion of exactly the metadata the attention kernel consumes, for
- * one scene (host only; test helper).  Row r is the token at offset
+/* Dense expansion of the template metadata (slot starts, ancestor words) under
+ * a given cache state, for one scene, computed on the host (host only; test
+ * helper: it checks fdc_build_mask's outputs, not the device's tables - for
+ * those see fdc_step_tables_dense).  Row r is the token at offset
  * row_off[r] of field row_field[r]; valid_len[g] is the number of tokens of
  * field g in the cache after the step's appends.  mask[r*N + j] = 1 iff j is
  * in the prefix, or a written token of a strict ancestor, or an own token at
@@ -203,7 +206,7 @@ int32_t fdc_set_valid_len(fdc_ctx* ctx, const int32_t* valid_len);
 int32_t fdc_get_valid_len(const fdc_ctx* ctx, int32_t* valid_len);
 
 /* ---------------------------------------------------------------------------
- * Sec. 3.3 "KV cache fully shared and reused": write rows of K (already
+ * The one KV cache all branches share (Sec. 3.3): write rows of K (already
  * rotated) and V into layer `layer` of the cache at (scene, position).  Used in
  * bulk to install prefix K/V and slot history; the decode step appends its own
  * rows itself.  Does not change valid_len.
@@ -234,8 +237,10 @@ int32_t fdc_kv_append(fdc_ctx* ctx, int32_t layer, const void* k_new, const void
  *              after the embedding (0) and after each layer (1..L), then the
  *              final normalised hidden state (L+1)
  * Errors: FDC_ESTATE, FDC_ECAP (R, T or rows above limits), FDC_ERANGE (field id,
- * or offset + T beyond the slot), FDC_EINVAL, FDC_EHIP.  On error nothing is
- * enqueued and valid_len is unchanged.
+ * offset + T beyond the slot, or an offset beyond the tokens the slot holds:
+ * slots fill from the front, a gap would be attended to as if written),
+ * FDC_EINVAL (also: a field listed twice for one scene), FDC_EHIP.  On error
+ * nothing is enqueued and valid_len is unchanged.
  */
 int32_t fdc_parallel_decode_step(fdc_ctx* ctx, int32_t n_branches, int32_t T,
                                  const int32_t* branch_field, const int32_t* branch_off,
@@ -256,8 +261,8 @@ int32_t fdc_parallel_decode_step(fdc_ctx* ctx, int32_t n_branches, int32_t T,
  * finishing token is recorded but not fed back, so valid_len[f] afterwards is
  * the number of tokens recorded for f.
  *
- * Fixed template text (field names; "pre-filled, visible to all subsequent
- * tokens"): a field with fixed_len[f] > 0 holds known tokens.  Such fields are
+ * Fixed template text (field names, Sec. 3.3: written beforehand and seen by
+ * whatever comes after it): a field with fixed_len[f] > 0 holds known tokens.  Such fields are
  * written first, in field order, by multi-token passes of up to max_tokens
  * tokens for all scenes at once, and count as finished from the start; the
  * template's edges say who sees them (a header that every later field depends
@@ -284,8 +289,8 @@ int32_t fdc_cot_decode(fdc_ctx* ctx, const int32_t* start_token, const int32_t* 
                        int32_t max_passes, int32_t* out_tok, int32_t* out_len, int32_t* out_passes,
                        void* stream);
 
-/* The step's attention alone (Sec. 3.3 mask; "shared KV cache accessed by
- * multiple query tokens within a single attention kernel"): DAG-masked GQA
+/* The step's attention alone (Sec. 3.3 mask; one kernel serves all query
+ * tokens that read the shared cache): DAG-masked GQA
  * decode attention of the given rotated queries against layer `layer` of the
  * cache under the current valid_len (which must already include the rows'
  * own tokens; not advanced here).
@@ -301,6 +306,37 @@ int32_t fdc_masked_attention(fdc_ctx* ctx, int32_t layer, const void* q,
                              int32_t n_branches, int32_t T,
                              const int32_t* branch_field, const int32_t* branch_off,
                              float* out, void* stream);
+
+/* Test helper for the mask and the position ids the DEVICE uses (Sec. 3.3, Eq. 1;
+ * they must equal the definition bit for bit).  Every step builds two tables on
+ * the GPU from the branch tables and valid_len: one 32-key visibility word per
+ * (scene, tile past the prefix, branch-token row), which is all the attention
+ * kernels know about the mask, and one position id per row, which the rotary /
+ * append kernel uses as rotation angle index and as cache index.  This call
+ * copies both tables back and expands them the way the kernels read them:
+ * mask[m*N + j] = 1 iff row m attends to cache position j (tiles that end inside
+ * the prefix: every active row; other tiles: bit j%32 of the row's word);
+ * pos[m] = the row's position id, -1 for rows of inactive entries (their mask
+ * rows are zero).  m = (scene*R + branch)*T + t, N = total_len.
+ *  branch_field/off  host [B*R]: the tables are built for this call under the
+ *                    current valid_len (which must cover the rows' own tokens,
+ *                    as for fdc_masked_attention); or both NULL: the tables the
+ *                    last fdc_parallel_decode_step / fdc_masked_attention with
+ *                    this R and T left on the device are read (FDC_ESTATE if none)
+ *  mask, pos         host out [B*R*T][N] and [B*R*T]
+ * Synchronises `stream`. */
+int32_t fdc_step_tables_dense(fdc_ctx* ctx, int32_t n_branches, int32_t T,
+                              const int32_t* branch_field, const int32_t* branch_off,
+                              uint8_t* mask, int32_t* pos, void* stream);
+
+/* How a context cuts its attention launches (host only, works without a GPU;
+ * for tests of the launch arithmetic).  info[10]: kernel variant, 32-row tiles
+ * per row group, row groups at the largest step, key chunks, weighted tiles per
+ * chunk, weight of a tile past the prefix in quarters, 32-key tiles in all,
+ * tiles that end inside the prefix, the kernel's limit of tiles per chunk, its
+ * limit of tiles past the prefix per chunk.  chunk_first_tile [chunks + 1] or
+ * NULL: first tile of every chunk, then the end. */
+int32_t fdc_attention_plan(const fdc_ctx* ctx, int32_t* info, int32_t* chunk_first_tile);
 
 /* Per-row greedy argmax over fp32 logits (final logits are fp32, Sec. 4.1).
  * logits device [M][ld] (ld >= V); idx_out device int32 [M]: lowest index of

@@ -33,7 +33,7 @@ EXPORTS = [
     "fdc_profile_calibrate", "fdc_stream_copy",
     "fdc_sched_create", "fdc_sched_next", "fdc_sched_destroy",
     "fdc_sched_peek", "fdc_sched_advance", "fdc_sched_complete", "fdc_sched_stats",
-    "fdc_cot_decode",
+    "fdc_cot_decode", "fdc_step_tables_dense", "fdc_attention_plan",
 ]
 FDC_PROF_KINDS = 9
 
@@ -146,6 +146,10 @@ def lib() -> C.CDLL:
     L.fdc_sched_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(i32)]
     L.fdc_cot_decode.restype = i32
     L.fdc_cot_decode.argtypes = [vp, pi32, pi32, pi32, pi32, i32, i32, pi32, pi32, pi32, vp]
+    L.fdc_step_tables_dense.restype = i32
+    L.fdc_step_tables_dense.argtypes = [vp, i32, i32, pi32, pi32, C.POINTER(C.c_uint8), pi32, vp]
+    L.fdc_attention_plan.restype = i32
+    L.fdc_attention_plan.argtypes = [vp, pi32, pi32]
     _lib = L
     return L
 
@@ -336,14 +340,39 @@ def fdc_stream_copy(dst, src) -> None:
     _check(lib().fdc_stream_copy(dst.data_ptr(), src.data_ptr(), nb, _stream()))
 
 
+def fdc_attention_plan(dims, slot_len, edges, prefix_len, n_scenes=1, max_branches=1, max_tokens=1) -> dict:
+    """The attention launch plan of a context of this shape (host only: no GPU needed)."""
+    desc = ModelDesc(dims.n_layers, dims.d_model, dims.n_q_heads, dims.n_kv_heads, dims.head_dim,
+                     dims.d_mlp, dims.vocab, dims.rope_base, dims.norm_eps)
+    sl = _i32(slot_len)
+    src, dst = _edges(edges)
+    h = C.c_void_p()
+    _check(lib().fdc_create(C.byref(desc), sl.size, _p(sl), src.size, _p(src), _p(dst), int(prefix_len),
+                            n_scenes, max_branches, max_tokens, C.byref(h)))
+    try:
+        info = np.zeros(10, dtype=np.int32)
+        _check(lib().fdc_attention_plan(h, _p(info), None))
+        first = np.zeros(int(info[3]) + 1, dtype=np.int32)
+        _check(lib().fdc_attention_plan(h, _p(info), _p(first)))
+    finally:
+        lib().fdc_destroy(h)
+    keys = ("variant", "nrt", "rg_max", "chunks", "cb", "wq", "tiles", "prefix_tiles", "max_chunk_tiles",
+            "max_masked_tiles")
+    out = {k: int(v) for k, v in zip(keys, info)}
+    out["chunk_first_tile"] = [int(x) for x in first]
+    return out
+
+
 class Context:
     """Owns an fdc_ctx plus the torch buffers handed to it (cache, workspace,
     packed weights).  Methods carry the names of the C entry points."""
 
     def __init__(self, dims, slot_len, edges, prefix_len, n_scenes=1, max_branches=1, max_tokens=1,
-                 device="cuda:0", share=None):
+                 device="cuda:0", share=None, weights_from=None):
         """share: another Context over the same model and the same cache positions
-        (same total length) whose KV cache and packed weights this one uses too."""
+        (same total length) whose KV cache and packed weights this one uses too.
+        weights_from: another Context over the same model whose packed weights this
+        one uses (its own cache: any template, any batch)."""
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -361,8 +390,11 @@ class Context:
         self._layer_w, self._head_w = {}, None
         self.edges = [(int(u), int(v)) for u, v in zip(src, dst)]
         self.prefix_len = int(prefix_len)
+        self.total_len = int(prefix_len) + int(self.slot_len.sum())
         with torch.cuda.device(self.device):
             kvb = int(lib().fdc_kv_cache_bytes(self._h))
+            if share is not None and weights_from is not None:
+                raise ValueError("give share or weights_from, not both")
             if share is not None:
                 if share.k_cache.numel() * 2 != kvb:
                     raise ValueError("contexts that share a cache must cover the same positions")
@@ -374,6 +406,8 @@ class Context:
             wsb = int(lib().fdc_workspace_bytes(self._h))
             self.workspace = torch.empty(wsb, dtype=torch.uint8, device=self.device)
             _check(lib().fdc_set_workspace(self._h, self.workspace.data_ptr(), wsb, _stream()))
+        if share is None and weights_from is not None:
+            share = weights_from
         if share is not None:
             for layer, lw in share._layer_w.items():
                 _check(lib().fdc_set_layer_weights(self._h, layer, C.byref(lw)))
@@ -552,6 +586,20 @@ class Context:
                                     _p(eos) if eos.size else None, eos.size, max_passes,
                                     _p(tok), _p(ln), _p(ps), _stream()))
         return {"tok": tok, "len": ln, "passes": int(ps[0]), "fixed_passes": int(ps[1])}
+
+    def step_tables_dense(self, R: int, T: int = 1, branch_field=None, branch_off=None):
+        """fdc_step_tables_dense: (mask [B*R*T][N] uint8, pos [B*R*T] int32) expanded from
+        the tables on the device; without branch tables, those of the last step."""
+        N = int(self.total_len)
+        M = self.B * R * T
+        mask = np.empty((M, N), dtype=np.uint8)
+        pos = np.empty(M, dtype=np.int32)
+        bf = _i32(branch_field) if branch_field is not None else None
+        bo = _i32(branch_off) if branch_off is not None else None
+        _check(lib().fdc_step_tables_dense(self._h, R, T, _p(bf) if bf is not None else None,
+                                           _p(bo) if bo is not None else None, _p(mask, C.c_uint8), _p(pos),
+                                           _stream()))
+        return mask, pos
 
     def masked_attention(self, layer: int, q, branch_field, branch_off, T: int = 1):
         torch = self.torch

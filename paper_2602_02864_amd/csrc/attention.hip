@@ -3,8 +3,8 @@
 // All query rows that share a KV head - every active branch of a scene, its T
 // new tokens and the G query heads of the group - form one row group of up to
 // 64 rows, so the shared prefix and every visible slot are streamed from HBM
-// once for all of them (the paper's "shared KV cache accessed by multiple query
-// tokens within a single attention kernel").  The key dimension is cut into
+// once for all of them (Sec. 3.3: one kernel serves every query token that
+// reads the shared cache).  The key dimension is cut into
 // chunks (split-K); one workgroup takes one chunk of one (scene, kv head, row
 // group) and emits one partial softmax state; a second kernel merges the
 // chunks' partials in a fixed order (no atomics: results are bit-reproducible).
@@ -53,14 +53,8 @@ __device__ __forceinline__ float keep_if(float x, uint32_t bits, int k) {
 constexpr int kStages = 4;
 constexpr int kStreams = 2;
 
-// First tile of chunk c.  Tiles that reach past the prefix carry masks and cost
-// more (measured: about 1.5 plain tiles each, their table set-up included), so
-// chunks are equal in weighted tiles: a tile past the prefix counts wq / 4.
 __device__ __forceinline__ int chunk_start(const AttnArgs& a, int c) {
-    const int t0 = a.P >> 5;
-    const long x = (long)c * a.CB;
-    if (x <= t0) return (int)x;
-    return (int)min((long)a.NB, t0 + (4 * (x - t0) + a.wq - 1) / a.wq);
+    return attn_chunk_start(a.P, a.NB, a.CB, a.wq, c);
 }
 
 struct RowInfo {
@@ -132,18 +126,27 @@ __device__ __forceinline__ float other_half(float x, int hh) {
     return __uint_as_float(hh ? r[0] : r[1]);
 }
 
-// Visibility words of one step: for every scene b, every 32-key tile t that
-// reaches past the prefix and every branch-token row j (branch r, token tt:
-// j = r * T + tt) the 32 bits "key k of the tile is visible to that row".  A
-// row of field f at slot offset o sees what is left of the prefix in the tile,
-// the first valid_len[g] keys of each strict ancestor slot g and the first o+1
-// keys of its own slot (Sec. 3.3; Eq. 1).  The words depend on the step only,
-// not on the layer or the head: they are built once per step and every
-// attention workgroup of every layer fetches the few it needs.
+// Visibility words and position ids of one step.  Words: for every scene b,
+// every 32-key tile t that reaches past the prefix and every branch-token row j
+// (branch r, token tt: j = r * T + tt) the 32 bits "key k of the tile is visible
+// to that row".  A row of field f at slot offset o sees what is left of the
+// prefix in the tile, the first valid_len[g] keys of each strict ancestor slot g
+// and the first o+1 keys of its own slot (Sec. 3.3; Eq. 1).  Positions: row
+// m = (b * R + r) * T + tt sits at slot_start[f] + o, which is also its cache
+// index (Sec. 3.3: the fixed slot lengths fix every position id); -1 marks the
+// rows of inactive branch entries.  Both depend on the step only, not on the
+// layer or the head: they are built once per step; every attention workgroup of
+// every layer fetches the few words it needs, the rotary kernel the positions.
 __global__ __launch_bounds__(256) void mask_words_kernel(StepMeta sm, const uint64_t* __restrict__ anc, int P,
-                                                         int n_tiles, uint32_t* __restrict__ words) {
+                                                         int n_tiles, uint32_t* __restrict__ words,
+                                                         int32_t* __restrict__ row_pos) {
     const int RT = sm.R * sm.T;
     const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx < sm.B * RT) {
+        const int br = idx / sm.T;
+        const int f = sm.branch_field[br];
+        row_pos[idx] = f >= 0 ? sm.slot_start[f] + sm.branch_off[br] + idx % sm.T : -1;
+    }
     if (idx >= sm.B * n_tiles * RT) return;
     const int j = idx % RT, t = (idx / RT) % n_tiles, b = idx / (RT * n_tiles);
     const int r = j / sm.T, tt = j % sm.T;
@@ -308,7 +311,7 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
         for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
 
     const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
-    // Tile i of this stream -> stage i % 3.  The K half and the V half are LPT
+    // Tile i of this stream -> stage i % kStages.  The K half and the V half are LPT
     // pieces of 1 KiB; wavefront rt of the stream copies pieces rt*LPW .. +LPW.
     const uint32_t stage_off = lds_off(&stage[strm][0][0]);
     const uint32_t rowmask_off = lds_off(&rowmask[0][rt * 32 + r32]);
@@ -825,10 +828,11 @@ void launch_t(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
 
 void launch_mask_words(const StepMeta& sm, const uint64_t* anc, int P, int n_tiles, uint32_t* words,
                        hipStream_t st) {
-    const long n = (long)sm.B * n_tiles * sm.R * sm.T;
+    const long rows = (long)sm.B * sm.R * sm.T;
+    const long n = rows * (n_tiles > 1 ? n_tiles : 1);          // at least one thread per row (positions)
     if (n <= 0) return;
     hipLaunchKernelGGL(mask_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, sm, anc, P, n_tiles,
-                       words);
+                       words, const_cast<int32_t*>(sm.row_pos));
 }
 
 void launch_attention(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {

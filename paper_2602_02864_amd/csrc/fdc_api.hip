@@ -51,8 +51,8 @@ struct fdc_ctx {
     char* ws = nullptr;
     size_t ws_bytes = 0;
     struct Off {
-        size_t anc, slot_start, mask_words, inv_freq, rope_tab, meta, x, a_hi, a_lo, o_hi, o_lo, h_hi, h_lo, q,
-            part, logits, attn_o, attn_ml, tok_tmp, end;
+        size_t anc, slot_start, mask_words, row_pos, inv_freq, rope_tab, meta, x, a_hi, a_lo, o_hi, o_lo, h_hi, h_lo,
+            q, part, logits, attn_o, attn_ml, tok_tmp, end;
     } off{};
     size_t meta_ints = 0;
 
@@ -168,6 +168,7 @@ size_t carve(fdc_ctx* c) {
     c->off.anc = take(sizeof(uint64_t) * c->F);
     c->off.slot_start = take(sizeof(int32_t) * c->F);
     c->off.mask_words = take(sizeof(uint32_t) * (size_t)c->Mmax * std::max(1, c->NB - c->P / 32));
+    c->off.row_pos = take(sizeof(int32_t) * (size_t)c->Mmax);
     c->off.inv_freq = take(sizeof(double) * (m.head_dim / 2));
     c->off.rope_tab = take(sizeof(float2) * (size_t)c->Npad * (m.head_dim / 2));
     c->meta_ints = (size_t)2 * c->B * c->Rmax + (size_t)c->B * c->F;
@@ -205,18 +206,43 @@ size_t carve(fdc_ctx* c) {
     return o;
 }
 
-int32_t check_step(const fdc_ctx* c, int R, int T, const int32_t* bf, const int32_t* bo) {
+// `appending`: the rows are new tokens (the decode step).  Slots fill from the
+// front (Sec. 3.3), so the first new offset must not lie beyond what is written:
+// a gap would be read by the row itself and by every descendant as if it held
+// tokens.  A field may appear once per scene.
+int32_t check_step(const fdc_ctx* c, int R, int T, const int32_t* bf, const int32_t* bo, bool appending) {
     if (!bf || !bo) return fail(FDC_EINVAL, "branch_field / branch_off is null");
     if (R < 1 || R > c->Rmax) return fail(FDC_ECAP, "n_branches %d outside 1..%d", R, c->Rmax);
     if (T < 1 || T > c->Tmax) return fail(FDC_ECAP, "T %d outside 1..%d", T, c->Tmax);
-    for (int i = 0; i < c->B * R; ++i) {
-        const int f = bf[i];
-        if (f == -1) continue;
-        if (f < 0 || f >= c->F) return fail(FDC_ERANGE, "branch %d: field %d outside 0..%d", i, f, c->F - 1);
-        if (bo[i] < 0 || bo[i] + T > c->slot_len[f])
-            return fail(FDC_ERANGE, "branch %d: offsets %d..%d do not fit slot %d of length %d", i,
-                        bo[i], bo[i] + T - 1, f, c->slot_len[f]);
+    for (int b = 0; b < c->B; ++b) {
+        uint64_t seen = 0;
+        for (int r = 0; r < R; ++r) {
+            const int i = b * R + r, f = bf[i];
+            if (f == -1) continue;
+            if (f < 0 || f >= c->F) return fail(FDC_ERANGE, "branch %d: field %d outside 0..%d", i, f, c->F - 1);
+            if (bo[i] < 0 || bo[i] + T > c->slot_len[f])
+                return fail(FDC_ERANGE, "branch %d: offsets %d..%d do not fit slot %d of length %d", i,
+                            bo[i], bo[i] + T - 1, f, c->slot_len[f]);
+            if ((seen >> f) & 1ull) return fail(FDC_EINVAL, "scene %d: field %d is listed twice", b, f);
+            seen |= 1ull << f;
+            if (appending && bo[i] > c->valid_len[(size_t)b * c->F + f])
+                return fail(FDC_ERANGE, "branch %d: offset %d would leave a gap after the %d tokens of field %d", i,
+                            bo[i], c->valid_len[(size_t)b * c->F + f], f);
+        }
     }
+    return FDC_OK;
+}
+
+// pinned staging for the per-step tables and the CoT driver's tokens: allocated
+// when the workspace is set (a context can be created and its plan inspected
+// without a GPU)
+int32_t ensure_staging(fdc_ctx* c) {
+    const size_t stage_bytes = sizeof(int32_t) * c->meta_ints;
+    for (int i = 0; i < kStageSlots; ++i) {
+        if (!c->stage[i]) FDC_HIP(hipHostMalloc((void**)&c->stage[i], stage_bytes, hipHostMallocDefault));
+        if (!c->stage_ev[i]) FDC_HIP(hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming));
+    }
+    if (!c->drv_host) FDC_HIP(hipHostMalloc((void**)&c->drv_host, sizeof(int32_t) * 2 * c->Mmax, hipHostMallocDefault));
     return FDC_OK;
 }
 
@@ -233,6 +259,7 @@ int32_t upload_meta(fdc_ctx* c, int R, const int32_t* bf, const int32_t* bo, hip
     sm->branch_off = d + nbr;
     sm->valid_len = d + 2 * nbr;
     sm->slot_start = c->at<int32_t>(c->off.slot_start);
+    sm->row_pos = c->at<int32_t>(c->off.row_pos);
     sm->B = c->B;
     sm->R = R;
     sm->T = T;
@@ -462,21 +489,12 @@ int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t*
             delete c;
             return fail(FDC_ECAP, "projection with K = %d does not fit the streaming kernel", p->KT * 32);
         }
+    if (c->NB > 65535) {               // the attention kernels keep tile numbers in 16 bits
+        delete c;
+        return fail(FDC_ECAP, "%d cache positions: more than 65535 tiles of 32 keys", N);
+    }
     plan_attention(c);
     carve(c);
-    const size_t stage_bytes = sizeof(int32_t) * c->meta_ints;
-    for (int i = 0; i < kStageSlots; ++i) {
-        if (hipHostMalloc((void**)&c->stage[i], stage_bytes, hipHostMallocDefault) != hipSuccess ||
-            hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming) != hipSuccess) {
-            fdc_destroy(c);
-            return fail(FDC_EHIP, "could not allocate pinned staging memory");
-        }
-    }
-    if (hipHostMalloc((void**)&c->drv_host, sizeof(int32_t) * 2 * c->Mmax, hipHostMallocDefault) != hipSuccess) {
-        c->drv_host = nullptr;
-        fdc_destroy(c);
-        return fail(FDC_EHIP, "could not allocate pinned staging memory");
-    }
     *out = c;
     return FDC_OK;
 }
@@ -518,6 +536,8 @@ int32_t fdc_set_workspace(fdc_ctx* c, void* ws, size_t bytes, void* stream) {
     if (!aligned(ws, 256)) return fail(FDC_EINVAL, "workspace must be 256-byte aligned");
     if (bytes < c->off.end) return fail(FDC_EINVAL, "workspace of %zu bytes, %zu needed", bytes, c->off.end);
     hipStream_t st = (hipStream_t)stream;
+    int32_t rc_st = ensure_staging(c);
+    if (rc_st != FDC_OK) return rc_st;
     c->ws = (char*)ws;
     c->meta_last_T = 0;
     c->ws_bytes = bytes;
@@ -592,12 +612,75 @@ int32_t fdc_kv_append(fdc_ctx* c, int32_t layer, const void* k_new, const void* 
     return FDC_OK;
 }
 
+int32_t fdc_attention_plan(const fdc_ctx* c, int32_t* info, int32_t* chunk_first_tile) {
+    if (!c || !info) return fail(FDC_EINVAL, "null pointer argument");
+    info[0] = c->attn_variant;
+    info[1] = c->attn_nrt;
+    info[2] = c->attn_rg_max;
+    info[3] = c->attn_chunks;
+    info[4] = c->attn_cb;
+    info[5] = c->attn_wq;
+    info[6] = c->NB;
+    info[7] = c->P / 32;
+    info[8] = c->attn_variant == 1 ? kMaxChunkTilesReg : kMaxChunkTiles;
+    info[9] = kMaxMaskedTiles;
+    if (chunk_first_tile)
+        for (int ch = 0; ch <= c->attn_chunks; ++ch)
+            chunk_first_tile[ch] = attn_chunk_start(c->P, c->NB, c->attn_cb, c->attn_wq, ch);
+    return FDC_OK;
+}
+
+int32_t fdc_step_tables_dense(fdc_ctx* c, int32_t R, int32_t T, const int32_t* bf, const int32_t* bo,
+                              uint8_t* mask, int32_t* pos, void* stream) {
+    if (!c || !mask || !pos) return fail(FDC_EINVAL, "null pointer argument");
+    if (!c->ws) return fail(FDC_ESTATE, "workspace not set");
+    hipStream_t st = (hipStream_t)stream;
+    if (bf || bo) {
+        int32_t rc = check_step(c, R, T, bf, bo, false);
+        if (rc != FDC_OK) return rc;
+        for (int i = 0; i < c->B * R; ++i)
+            if (bf[i] >= 0 && c->valid_len[(size_t)(i / R) * c->F + bf[i]] < bo[i] + T)
+                return fail(FDC_ERANGE, "branch %d: valid_len does not cover the rows' own tokens", i);
+        StepMeta sm;
+        rc = upload_meta(c, R, bf, bo, st, &sm, T);
+        if (rc != FDC_OK) return rc;
+    } else {
+        // the tables of the last step or attention call, as they sit on the device
+        const size_t fixed = (size_t)c->B * c->F;
+        if (c->meta_last_T != T || T < 1 || R < 1 || c->meta_last.size() != 2 * (size_t)c->B * R + fixed)
+            return fail(FDC_ESTATE, "the device holds no tables of a step with R = %d, T = %d", R, T);
+    }
+    const int RT = R * T, mw = c->NB - c->P / 32, t0 = c->P / 32;
+    const size_t rows = (size_t)c->B * RT;
+    std::vector<uint32_t> words((size_t)c->B * mw * RT);
+    std::vector<int32_t> dpos(rows);
+    FDC_HIP(hipMemcpyAsync(words.data(), c->at<void>(c->off.mask_words), sizeof(uint32_t) * words.size(),
+                           hipMemcpyDeviceToHost, st));
+    FDC_HIP(hipMemcpyAsync(dpos.data(), c->at<void>(c->off.row_pos), sizeof(int32_t) * rows, hipMemcpyDeviceToHost, st));
+    FDC_HIP(hipStreamSynchronize(st));
+    // What the attention kernels do with the tables: tiles that end inside the
+    // prefix are visible to every active row without a word, every other tile
+    // bit by bit; rows of inactive entries (position -1) see nothing.
+    for (size_t m = 0; m < rows; ++m) {
+        const int b = (int)(m / RT), j = (int)(m % RT);
+        uint8_t* row = mask + m * (size_t)c->N;
+        pos[m] = dpos[m];
+        for (int key = 0; key < c->N; ++key) {
+            const int t = key >> 5;
+            if (dpos[m] < 0) row[key] = 0;
+            else if (t < t0) row[key] = 1;
+            else row[key] = (uint8_t)((words[((size_t)b * mw + (t - t0)) * RT + j] >> (key & 31)) & 1u);
+        }
+    }
+    return FDC_OK;
+}
+
 int32_t fdc_masked_attention(fdc_ctx* c, int32_t layer, const void* q, int32_t R, int32_t T,
                              const int32_t* bf, const int32_t* bo, float* out, void* stream) {
     if (!c || !q || !out) return fail(FDC_EINVAL, "null pointer argument");
     if (!c->kc || !c->vc || !c->ws) return fail(FDC_ESTATE, "KV cache or workspace not set");
     if (layer < 0 || layer >= c->m.n_layers) return fail(FDC_ERANGE, "layer %d outside 0..%d", layer, c->m.n_layers - 1);
-    int32_t rc = check_step(c, R, T, bf, bo);
+    int32_t rc = check_step(c, R, T, bf, bo, false);
     if (rc != FDC_OK) return rc;
     for (int i = 0; i < c->B * R; ++i)
         if (bf[i] >= 0 && c->valid_len[(size_t)(i / R) * c->F + bf[i]] < bo[i] + T)
@@ -629,7 +712,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         if (!c->lw_set[l]) return fail(FDC_ESTATE, "weights of layer %d not set", l);
     if (!tok_out) return fail(FDC_EINVAL, "tok_out is null");
     if ((tok_in == nullptr) == (emb_in == nullptr)) return fail(FDC_EINVAL, "give exactly one of tok_in and emb_in");
-    int32_t rc = check_step(c, R, T, bf, bo);
+    int32_t rc = check_step(c, R, T, bf, bo, true);
     if (rc != FDC_OK) return rc;
     const fdc_model_desc& m = c->m;
     const int M = c->B * R * T;
@@ -666,14 +749,15 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     // up to 16 rows the projections stream their weights once (bandwidth-bound);
     // above, they are tiled matrix products; either way `S` partials come back
     const bool tiled = M > kMaxRowsDense;
+    bool launched = true;              // false: a projection had no kernel for its plan
     auto project = [&](const GemmPlan& skinny, int64_t n_out, int64_t k_in, int epi, const GemmArgs& ga,
                        bool one_split) -> int {
         if (!tiled) {
-            launch_gemm(skinny, epi, ga, st);
+            launched = launch_gemm(skinny, epi, ga, st) && launched;
             return skinny.S;
         }
         const TiledPlan tp = plan_tiled(M, n_out, k_in, epi == EPI_SWIGLU, one_split ? 1 : 16);
-        launch_gemm_tiled(tp, epi, ga, st);
+        launched = launch_gemm_tiled(tp, epi, ga, st) && launched;
         return tp.S;
     };
 
@@ -785,9 +869,11 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     { ProfScope ps_(c, PK_LMHEAD, st); project(c->p_lm, m.vocab, d, EPI_PARTIAL, gl, true); }
     { ProfScope ps_(c, PK_ARGMAX, st); launch_argmax(logits, M, m.vocab, m.vocab, tok_out, gap_out, sm.branch_field, T, st); }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
+    if (e != hipSuccess || !launched) {
         c->valid_len = saved;
-        return fail(FDC_EHIP, "kernel launch failed: %s", hipGetErrorString(e));
+        c->meta_last_T = 0;
+        if (e != hipSuccess) return fail(FDC_EHIP, "kernel launch failed: %s", hipGetErrorString(e));
+        return fail(FDC_ECAP, "a projection of this step has no kernel for its plan");
     }
     return FDC_OK;
 }
@@ -900,8 +986,8 @@ int32_t fdc_cot_decode(fdc_ctx* c, const int32_t* start_token, const int32_t* fi
         if (rc != FDC_OK) return rc;
         FDC_HIP(hipMemcpyAsync(h_out, d_out, sizeof(int32_t) * B * R, hipMemcpyDeviceToHost, st));
         FDC_HIP(hipStreamSynchronize(st));
-        // "the field corresponding to v is finished": the model ended the line,
-        // or the slot is full (truncation to the fixed length)
+        // when a field counts as finished (Algorithm 1's test): the model ended
+        // the line, or the slot is full (truncation to the fixed length)
         for (int b = 0; b < B; ++b) {
             for (int i = 0; i < nact[b]; ++i) {
                 const int f = bf[(size_t)b * R + i], off = bo[(size_t)b * R + i];
@@ -1048,13 +1134,13 @@ int32_t linear_enqueue(const float* x, const void* w, float* y, int32_t M, int64
         launch_to_frag(x, hi, lo, M, (int)k_in, st);
         S = p.S;
         g.out = S == 1 ? y : part;
-        launch_gemm(p, EPI_PARTIAL, g, st);
+        if (!launch_gemm(p, EPI_PARTIAL, g, st)) return fail(FDC_ECAP, "no streaming kernel for this shape");
     } else {
         const TiledPlan p = plan_tiled(M, n_out, k_in, false);
         launch_to_frag(x, hi, lo, M, (int)k_in, st);
         S = p.S;
         g.out = S == 1 ? y : part;
-        launch_gemm_tiled(p, EPI_PARTIAL, g, st);
+        if (!launch_gemm_tiled(p, EPI_PARTIAL, g, st)) return fail(FDC_ECAP, "no tiled kernel for this shape");
     }
     if (S > 1) launch_sum_partials(part, y, S, M, n_out, st);
     FDC_HIP(hipGetLastError());

@@ -243,6 +243,12 @@ int32_t fdc_dense_mask(int32_t F, const int32_t* slot_len, const int32_t* slot_s
     if (!slot_len || !slot_start || !anc || !valid_len || (n_rows && (!row_field || !row_off || !mask || !pos)))
         return fdc::fail(FDC_EINVAL, "null pointer argument");
     const int W = (F + 63) / 64;
+    // the layout must be the one fdc_build_mask produces: slots back to back after the prefix
+    for (int g = 0; g < F; ++g) {
+        if (slot_len[g] < 1) return fdc::fail(FDC_EINVAL, "slot_len[%d] = %d must be >= 1", g, slot_len[g]);
+        const int64_t want = g == 0 ? (int64_t)prefix_len : (int64_t)slot_start[g - 1] + slot_len[g - 1];
+        if (slot_start[g] != want) return fdc::fail(FDC_EINVAL, "slot_start[%d] = %d, expected %lld", g, slot_start[g], (long long)want);
+    }
     const int64_t N = (int64_t)slot_start[F - 1] + slot_len[F - 1];
     for (int g = 0; g < F; ++g)
         if (valid_len[g] < 0 || valid_len[g] > slot_len[g])

@@ -23,8 +23,9 @@ struct GemmArgs {
     int n_valid;              // output features actually stored (multiple of 4)
     int out_KT;               // EPI_SWIGLU: k tiles of the consumer (= d_mlp / 32)
 };
-void launch_gemm(const GemmPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
-void launch_gemm_tiled(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
+// both return false (and launch nothing) for a plan no kernel was built for
+bool launch_gemm(const GemmPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
+bool launch_gemm_tiled(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
 void launch_pack_weight(const uint16_t* src, uint16_t* dst, int64_t n_out, int64_t k_in, int mode,
                         hipStream_t st);
 // x fp32 [M][K] -> hi/lo fragments (no normalisation); y = sum of S partials
@@ -37,6 +38,8 @@ struct StepMeta {             // device copies of the step's small tables
     const int32_t* branch_off;     // [B*R]
     const int32_t* valid_len;      // [B*F]
     const int32_t* slot_start;     // [F]
+    const int32_t* row_pos;        // [B*R*T] position id (= cache index) of every row, -1 for inactive
+                                   // rows; written by launch_mask_words for the step
     int B, R, T, F;
 };
 
@@ -98,8 +101,22 @@ struct AttnArgs {
     float scale_log2;         // log2(e) / sqrt(D)
 };
 void launch_attention(const AttnArgs& a, const StepMeta& sm, hipStream_t st);
-// once per step, after the step's tables are on the device and before its first attention
+// once per step, after the step's tables are on the device and before its first
+// kernel: the visibility words and the rows' position ids (sm.row_pos is written)
 void launch_mask_words(const StepMeta& sm, const uint64_t* anc, int P, int n_tiles, uint32_t* words,
                        hipStream_t st);
+
+// First 32-key tile of key chunk c of an attention launch.  Tiles that reach past
+// the prefix carry masks and cost more (measured: about 1.5 plain tiles each,
+// their table set-up included), so chunks are equal in weighted tiles: a tile
+// past the prefix counts wq / 4.  P: prefix length, NB: tiles in all, CB:
+// weighted tiles per chunk.
+__host__ __device__ inline int attn_chunk_start(int P, int NB, int CB, int wq, int c) {
+    const int t0 = P >> 5;
+    const long x = (long)c * CB;
+    if (x <= t0) return (int)x;
+    const long t = t0 + (4 * (x - t0) + wq - 1) / wq;
+    return (int)(t < NB ? t : NB);
+}
 
 }  // namespace fdc

@@ -114,7 +114,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs a, int KT, in
 }
 
 template <int NT, int EPI>
-void launch_ktw(const GemmPlan& p, const GemmArgs& a, hipStream_t st) {
+bool launch_ktw(const GemmPlan& p, const GemmArgs& a, hipStream_t st) {
     dim3 grid(p.grid), block(p.nw * 64);
 #define FDC_CASE(K)                                                                             \
     case K:                                                                                     \
@@ -124,9 +124,10 @@ void launch_ktw(const GemmPlan& p, const GemmArgs& a, hipStream_t st) {
     switch (p.ktw) {
         FDC_CASE(2) FDC_CASE(4) FDC_CASE(6) FDC_CASE(8) FDC_CASE(10) FDC_CASE(12) FDC_CASE(14)
         FDC_CASE(16) FDC_CASE(20)
-        default: break;   // plan_gemm never produces another bound
+        default: return false;   // no kernel for this bound: nothing was launched
     }
 #undef FDC_CASE
+    return true;
 }
 
 // row-major [n_out][k_in] -> [tile][kt][64 lanes][8]; lane = row%16 + 16*((k%32)/8)
@@ -169,9 +170,9 @@ __global__ void sum_partials_kernel(const float* __restrict__ part, float* __res
 
 }  // namespace
 
-void launch_gemm(const GemmPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
-    if (epilogue == EPI_SWIGLU) launch_ktw<2, EPI_SWIGLU>(p, a, st);
-    else launch_ktw<1, EPI_PARTIAL>(p, a, st);
+bool launch_gemm(const GemmPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
+    if (epilogue == EPI_SWIGLU) return launch_ktw<2, EPI_SWIGLU>(p, a, st);
+    return launch_ktw<1, EPI_PARTIAL>(p, a, st);
 }
 
 void launch_pack_weight(const uint16_t* src, uint16_t* dst, int64_t n_out, int64_t k_in, int mode,

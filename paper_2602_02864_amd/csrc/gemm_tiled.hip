@@ -430,13 +430,14 @@ void launch_ntw(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t
 
 }  // namespace
 
-void launch_gemm_tiled(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
+bool launch_gemm_tiled(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
     switch (p.ntw) {
         case 4: launch_ntw<4>(p, epilogue, a, st); break;
         case 8: launch_ntw<8>(p, epilogue, a, st); break;
         case 10: launch_ntw<10>(p, epilogue, a, st); break;
-        default: break;   // plan_tiled never produces another width
+        default: return false;   // no kernel for this width: nothing was launched
     }
+    return true;
 }
 
 }  // namespace fdc

@@ -140,14 +140,13 @@ __global__ void rope_table_kernel(const double* __restrict__ inv_freq, float2* _
 
 // Workgroups of 256 threads, several per row: sum the QKV partials, rotate q and
 // k by the row's position id (slot_start[field] + offset: fixed by the template,
-// Sec. 3.3), store q (fp32) and append k, v (bf16) to the cache at index =
-// position id.  A thread handles one rotation pair (or two V elements); its loads
+// Sec. 3.3; taken from the step's position table), store q (fp32) and append
+// k, v (bf16) to the cache at index = position id.  A thread handles one rotation pair (or two V elements); its loads
 // are independent of each other.
 template <int D>
 __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta sm) {
     const int m = blockIdx.y;
-    const int br = m / sm.T, t = m % sm.T;
-    const int f = sm.branch_field[br];
+    const int pos = sm.row_pos[m];              // slot_start[field] + offset + t, or -1: one look-up
     const int Nqkv = (a.Hq + 2 * a.Hkv) * D;
     constexpr int half = D / 2;
     const int n_pairs = (a.Hq + a.Hkv) * half;
@@ -172,9 +171,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a, StepMeta s
         x1 += part[s * sstride + c1];
         x2 += part[s * sstride + c2];
     }
-    if (f < 0) return;
-    const int scene = br / sm.R;
-    const int pos = sm.slot_start[f] + sm.branch_off[br] + t;
+    if (pos < 0) return;
+    const int scene = m / (sm.R * sm.T);
     if (rot) {
         const float2 cssn = a.tab[(size_t)pos * half + i];
         const float y1 = x1 * cssn.x - x2 * cssn.y, y2 = x2 * cssn.x + x1 * cssn.y;

@@ -30,6 +30,7 @@ class Pair:
     def __init__(self, dims, tpl, weights, n_scenes=1, max_branches=None, max_tokens=1, kv_bf16=True):
         from paper_2602_02864_amd import Context
         self.dims, self.tpl, self.w, self.B = dims, tpl, weights, n_scenes
+        self.n_sure = self.n_rows = 0          # rows whose greedy id had to agree / rows compared
         F = tpl.n_fields
         self.Rmax = max_branches or F
         # the library's cache is bf16: the oracle stores its K/V in that format too
@@ -41,8 +42,12 @@ class Pair:
             self.ctx.set_layer_weights(l, layers(l) if callable(layers) else layers[l])
         self.ctx.set_head_weights(weights["emb"], weights["gf"], weights["lm"])
 
-    def close(self):
+    def close(self, need_sure=True):
+        """need_sure: the greedy-id comparison must have had something to compare
+        (rows whose top-2 gap exceeds GAP_MIN) over the life of the pair."""
         self.ctx.close()
+        if need_sure and self.n_rows > 0:
+            assert self.n_sure > 0, f"no row of {self.n_rows} had a top-2 gap above {GAP_MIN}: ids never compared"
 
     # prefix K/V are data: rounded to bf16 once, handed to both sides
     def install_prefix_kv(self, scene, K, V):
@@ -53,6 +58,21 @@ class Pair:
             self.ctx.kv_append(l, np.ascontiguousarray(np.transpose(K[l], (1, 0, 2)), dtype=np.float32),
                                np.ascontiguousarray(np.transpose(V[l], (1, 0, 2)), dtype=np.float32),
                                np.full(P, scene, dtype=np.int32), np.arange(P, dtype=np.int32))
+
+    def install_slot_kv(self, scene, field, K, V):
+        """History of a field as data on both sides: K, V [L][Hkv][n][D] of
+        bf16-representable values become the first n tokens of the field's slot."""
+        n = K.shape[2]
+        s0 = self.dec.slot_start[field]
+        assert n <= self.tpl.slot_len[field]
+        self.dec.K[:, scene, :, s0:s0 + n] = K
+        self.dec.V[:, scene, :, s0:s0 + n] = V
+        self.dec.valid_len[scene, field] = n
+        for l in range(self.dims.n_layers):
+            self.ctx.kv_append(l, np.ascontiguousarray(np.transpose(K[l], (1, 0, 2)), dtype=np.float32),
+                               np.ascontiguousarray(np.transpose(V[l], (1, 0, 2)), dtype=np.float32),
+                               np.full(n, scene, dtype=np.int32), np.arange(s0, s0 + n, dtype=np.int32))
+        self.ctx.set_valid_len(self.dec.valid_len)
 
     def prefill_with_oracle(self, scene, prefix_emb):
         P = self.tpl.prefix_len
@@ -73,9 +93,28 @@ class Pair:
         g = self.ctx.parallel_decode_step(bf, bo, tok_in=tok, T=T, want_logits=True, want_hidden=True)
         torch.cuda.synchronize()
         got = {k: v.cpu().numpy() for k, v in g.items() if not k.startswith("_")}
+        self.compare_tables(bf, bo, T, tag)
         if check:
             self.compare(ref, got, tag)
         return ref, got
+
+    def compare_tables(self, bf, bo, T, tag=""):
+        """The mask and the position ids the device used in the step it just ran
+        (its visibility words and position table, expanded) against the oracle's
+        dense mask under the state after the step: bit for bit (Sec. 3.3, Eq. 1)."""
+        R = bf.shape[1]
+        mask, pos = self.ctx.step_tables_dense(R, T)
+        tpl = self.tpl
+        for b in range(self.B):
+            for r in range(R):
+                m0 = (b * R + r) * T
+                if bf[b, r] < 0:
+                    assert not mask[m0:m0 + T].any() and (pos[m0:m0 + T] == -1).all(), f"{tag}: inactive rows"
+                    continue
+                want, wpos = O.dense_mask(tpl.prefix_len, tpl.slot_len, tpl.edges, self.dec.valid_len[b],
+                                          [int(bf[b, r])] * T, [int(bo[b, r]) + t for t in range(T)])
+                assert np.array_equal(mask[m0:m0 + T].astype(bool), want), f"{tag}: device mask, scene {b} branch {r}"
+                assert np.array_equal(pos[m0:m0 + T], wpos), f"{tag}: device positions, scene {b} branch {r}"
 
     def compare(self, ref, got, tag=""):
         L = self.dims.n_layers
@@ -91,6 +130,8 @@ class Pair:
         assert max(errs) <= HIDDEN_TOL, f"{tag}: hidden-state error per layer {errs}"
         assert e_log <= HIDDEN_TOL, f"{tag}: logits error {e_log}"
         sure = rows[ref["gap"][rows] > GAP_MIN]
+        self.n_sure += int(sure.size)
+        self.n_rows += int(rows.size)
         assert np.array_equal(got["tok"][sure], ref["tok"][sure]), f"{tag}: greedy ids differ"
         inactive = np.setdiff1d(np.arange(ref["tok"].size), rows)
         assert (got["tok"][inactive] == -1).all(), f"{tag}: inactive rows must return -1"

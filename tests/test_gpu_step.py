@@ -217,6 +217,78 @@ def test_workload4_shapes_one_layer_256_rows():
     pair.close()
 
 
+def _cfg_head_weights(cfg_id, dims):
+    rng = workload_seed(cfg_id, "weights", 0)
+    return {"emb": draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02),
+            "gf": draw_normal_bf16(rng, (dims.d_model,), 0.02, 1.0),
+            "lm": draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)}
+
+
+def test_workload4_all_active_1024_rows_full_width():
+    """The all-active half of workload 4 at full width, in the launch shape the
+    benchmark's stress run times: 8 scenes x 32 fields x 4 tokens = 1024 rows
+    through one 7B-class layer, prefix 8192, fourteen row groups per KV head.
+    Every slot already holds 12 tokens (history installed as data on both sides),
+    so every field attends to 16 tokens of each of its ancestors.  The device's
+    mask and positions are compared for all 1024 rows; hidden states and logits
+    against the oracle on two of the eight scenes (scenes are independent; the
+    oracle takes about a minute per four scenes)."""
+    dims = model_dims(4, n_layers=1)
+    tpl = template(4)
+    w = {"layers": [draw_layer_weights(4, dims, 0, random_gains=True)], **_cfg_head_weights(4, dims)}
+    B, R, T, hist = 8, tpl.n_fields, 4, 12
+    sample = [1, 6]
+    pair = Pair(dims, tpl, w, n_scenes=B, max_branches=R, max_tokens=T)
+    sub = O.OracleDecoder(dims, w, tpl.prefix_len, tpl.slot_len, tpl.edges, len(sample), kv_bf16=True)
+    shp = (dims.n_layers, dims.n_kv_heads, tpl.prefix_len, dims.head_dim)
+    hshp = (dims.n_layers, dims.n_kv_heads, hist, dims.head_dim)
+    for b in range(B):
+        prng = workload_seed(4, "prefix", 50 + b)
+        K, V = draw_normal_bf16(prng, shp), draw_normal_bf16(prng, shp)
+        hk = [(draw_normal_bf16(prng, hshp), draw_normal_bf16(prng, hshp)) for _ in range(R)]
+        if b in sample:
+            i = sample.index(b)
+            sub.set_prefix_kv(i, K, V)
+            for f, (k, v) in enumerate(hk):
+                s0 = sub.slot_start[f]
+                sub.K[:, i, :, s0:s0 + hist], sub.V[:, i, :, s0:s0 + hist] = k, v
+        # the full-batch oracle object only carries state (valid lengths) for the table check
+        for l in range(dims.n_layers):
+            pos = np.concatenate([np.arange(tpl.prefix_len)] +
+                                 [np.arange(pair.dec.slot_start[f], pair.dec.slot_start[f] + hist) for f in range(R)])
+            kk = np.concatenate([K[l]] + [k[l] for k, _ in hk], axis=1)
+            vv = np.concatenate([V[l]] + [v[l] for _, v in hk], axis=1)
+            pair.ctx.kv_append(l, np.ascontiguousarray(np.transpose(kk, (1, 0, 2)), dtype=np.float32),
+                               np.ascontiguousarray(np.transpose(vv, (1, 0, 2)), dtype=np.float32),
+                               np.full(pos.size, b, dtype=np.int32), pos.astype(np.int32))
+    pair.dec.valid_len[:] = hist
+    sub.valid_len[:] = hist
+    pair.ctx.set_valid_len(pair.dec.valid_len)
+    trng = np.random.default_rng(45)
+    bf = np.tile(np.arange(R, dtype=np.int32), (B, 1))
+    bo = np.full((B, R), hist, dtype=np.int32)
+    tok = trng.integers(0, dims.vocab, size=(B, R, T)).astype(np.int32)
+    import torch
+    g = pair.ctx.parallel_decode_step(bf, bo, tok_in=tok, T=T, want_logits=True, want_hidden=True)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in g.items() if not k.startswith("_")}
+    pair.dec.valid_len[:] = hist + T                    # what the step leaves behind
+    assert np.array_equal(pair.ctx.get_valid_len(), pair.dec.valid_len)
+    pair.compare_tables(bf, bo, T, "cfg4 all active")   # all 1024 rows, bit for bit
+    assert np.isfinite(got["logits"]).all()
+    ref = sub.step(bf[sample], bo[sample], tok_in=tok[sample], T=T)
+    rows_g = np.concatenate([np.arange(b * R * T, (b + 1) * R * T) for b in sample])
+    L = dims.n_layers
+    errs = [rel_err(got["hidden"][l][rows_g], ref["hidden"][l]) for l in range(L + 1)]
+    errs.append(rel_err(got["hidden"][L + 1][rows_g], ref["normed"]))
+    errs.append(rel_err(got["logits"][rows_g], ref["logits"]))
+    assert max(errs) <= HIDDEN_TOL, errs
+    sure = np.nonzero(ref["gap"] > 1e-2)[0]
+    assert sure.size > 0
+    assert np.array_equal(got["tok"][rows_g][sure], ref["tok"][sure])
+    pair.close(need_sure=False)
+
+
 def test_step_error_paths_leave_state_unchanged():
     from paper_2602_02864_amd import FdcError, binding as fb
     dims = model_dims(0)
@@ -227,7 +299,9 @@ def test_step_error_paths_leave_state_unchanged():
     for args, code in [(([0, 1, 2, 3, 0], [0] * 5), fb.FDC_ECAP),        # R above max_branches
                        (([4], [0]), fb.FDC_ERANGE),                       # field id
                        (([0], [8]), fb.FDC_ERANGE),                       # offset beyond slot
-                       (([0], [-1]), fb.FDC_ERANGE)]:
+                       (([0], [-1]), fb.FDC_ERANGE),
+                       (([0], [3]), fb.FDC_ERANGE),                       # a gap: the slot holds no tokens yet
+                       (([1, 1], [0, 0]), fb.FDC_EINVAL)]:                # one field twice in a scene
         with pytest.raises(FdcError) as e:
             ctx.parallel_decode_step(args[0], args[1], tok_in=[0] * len(args[0]))
         assert e.value.code == code
@@ -255,22 +329,59 @@ def test_repeated_runs_are_bit_identical():
     pair.close()
 
 
-def test_workload2_full_depth_first_passes():
-    """The benchmarked configuration at full size: all 28 layers at 7B-class
-    widths, prefix 3072, the first two passes of the schedule (8 branches each).
-    The oracle stores K/V in the cache's bf16 format; a second oracle that keeps
-    fp64 K/V bounds what that storage format costs."""
+def _curve_file(name, lines):
+    """Per-layer error curves of a full-depth run, kept as a record: written under
+    gpurun_out/ (the folder that comes back from a GPU run)."""
+    import os
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    os.makedirs(d, exist_ok=True)
+    with open(os.path.join(d, f"parity_error_curve_{name}.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
+def _both_oracles_step(pair, plain, bf, bo, ti, tag, curves):
+    """One teacher-forced step on the GPU, on the oracle that stores K/V as bf16
+    (the graded comparison) and on the oracle that keeps fp64 K/V (what the
+    storage format costs).  Appends the three per-layer curves to `curves`."""
+    L = pair.dims.n_layers
+    ref, got = pair.step_both([bf], [bo], ti, check=False)
+    worst = pair.compare(ref, got, tag)
+    ref2 = plain.step([bf], [bo], tok_in=np.array(ti).reshape(1, -1, 1))
+    rows = ref2["rows"]
+    e_store = [rel_err(got["hidden"][l][rows], ref["hidden"][l][rows]) for l in range(L + 1)]
+    e_plain = [rel_err(got["hidden"][l][rows], ref2["hidden"][l][rows]) for l in range(L + 1)]
+    e_fmt = [rel_err(ref["hidden"][l][rows], ref2["hidden"][l][rows]) for l in range(L + 1)]
+    curves.append((tag, e_store, e_plain, e_fmt))
+    # what separates the GPU from the fp64-K/V oracle is the storage format: the two
+    # oracles differ by as much
+    assert max(e_plain) <= 1.1 * max(e_fmt) + ARITH_BOUND, (tag, max(e_plain), max(e_fmt))
+    return ref, worst, max(e_plain), max(e_fmt)
+
+
+def _curve_lines(title, curves):
+    out = [title, "columns: layer | GPU vs oracle with bf16 K/V storage | GPU vs oracle with fp64 K/V | "
+                  "oracle bf16-storage vs oracle fp64 (the storage format alone, CPU only)",
+           "metric: max|a - b| / max|b| over the residual stream after each layer (layer 0 = embedding)"]
+    for tag, e_store, e_plain, e_fmt in curves:
+        out.append(f"-- {tag}")
+        out += [f"{l:3d} {a:.3e} {b:.3e} {c:.3e}" for l, (a, b, c) in enumerate(zip(e_store, e_plain, e_fmt))]
+    return out
+
+
+_CFG2_BITS = []
+
+
+def _cfg2_full_depth():
     from synth_inputs import bits_to_f32
     dims = model_dims(2)
     tpl = template(2)
-    bits = [draw_layer_weights(2, dims, l, random_gains=True, bits=True) for l in range(dims.n_layers)]
+    if not _CFG2_BITS:          # 6.5 GB of bf16 patterns, drawn once for the tests that use them
+        _CFG2_BITS.extend(draw_layer_weights(2, dims, l, random_gains=True, bits=True) for l in range(dims.n_layers))
+    bits = _CFG2_BITS
 
     def layer(l):
         return {k: (bits_to_f32(v) if v.dtype == np.uint16 else v) for k, v in bits[l].items()}
-    rng = workload_seed(2, "weights", 0)
-    w = {"layers": layer, "emb": draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02),
-         "gf": draw_normal_bf16(rng, (dims.d_model,), 0.02, 1.0),
-         "lm": draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)}
+    w = {"layers": layer, **_cfg_head_weights(2, dims)}
     pair = Pair(dims, tpl, w)
     plain = O.OracleDecoder(dims, w, tpl.prefix_len, tpl.slot_len, tpl.edges, kv_bf16=False)
     prng = workload_seed(2, "prefix", 50)
@@ -278,37 +389,118 @@ def test_workload2_full_depth_first_passes():
     K, V = draw_normal_bf16(prng, shp), draw_normal_bf16(prng, shp)
     pair.install_prefix_kv(0, K, V)
     plain.set_prefix_kv(0, K, V)
+    return dims, tpl, pair, plain, prng
+
+
+# Bounds of the full-depth runs.  Against the oracle that stores K/V as bf16 the
+# arithmetic alone is compared and must stay far inside the 2e-3 budget.  Against
+# the oracle that keeps fp64 K/V the rounding of newly stored K/V to the cache's
+# bf16 format is included: that comparison is bounded by what was measured plus
+# ten per cent, and the oracles' own difference (CPU only) shows the format
+# accounts for it.
+ARITH_BOUND = 5e-4
+PLAIN_BOUND_CFG2 = 2.3e-3      # measured 2.09e-3 (first pass, layer 27); the oracles differ by the same 2.09e-3
+PLAIN_BOUND_CFG1 = 9.0e-4      # measured 7.8e-4 (first pass of the dependent fields, layer 24)
+
+
+def test_workload2_full_depth_first_passes():
+    """The benchmarked configuration at full size: all 28 layers at 7B-class
+    widths, prefix 3072, the first two passes of the schedule (8 branches each),
+    against both oracles, layer by layer."""
+    dims, tpl, pair, plain, _ = _cfg2_full_depth()
     steps = O.schedule(tpl.n_fields, tpl.edges, tpl.content_len)[:2]
     last = list(tpl.start_token)
+    curves = []
     for si, st in enumerate(steps):
         bf = [f for f, _ in st]
-        bo = [o for _, o in st]
-        ti = [last[f] for f, _ in st]
-        ref, got = pair.step_both([bf], [bo], ti, check=False)
-        worst = pair.compare(ref, got, f"cfg2 full depth pass {si}")
-        assert worst < 5e-4, worst          # arithmetic alone: far inside the 2e-3 budget
-        ref2 = plain.step([bf], [bo], tok_in=np.array(ti).reshape(1, -1, 1))
-        rows = ref2["rows"]
-        e2 = max(rel_err(got["hidden"][l][rows], ref2["hidden"][l][rows]) for l in range(dims.n_layers + 1))
-        assert e2 < 3e-3, e2                # bf16 storage of the new K/V included
-        for i, (f, _) in enumerate(st):
+        ref, worst, e_plain, e_fmt = _both_oracles_step(pair, plain, bf, [o for _, o in st], [last[f] for f in bf],
+                                                        f"cfg2 full depth, pass {si}: 8 roots at offset {si}", curves)
+        assert worst < ARITH_BOUND, worst
+        assert e_plain < PLAIN_BOUND_CFG2, e_plain
+        for i, f in enumerate(bf):
             last[f] = int(ref["tok"][i])
+    _curve_file("cfg2_first_passes", _curve_lines("workload 2 (28 layers, 7B-class widths), first passes", curves))
+    pair.close()
+
+
+def test_workload2_full_depth_later_passes():
+    """Later passes of workload 2 at all 28 layers: the three middle fields (R = 3,
+    each seeing 2-4 complete root fields) and the final field (R = 1, seeing all
+    eleven others).  The fields they depend on are installed as data (random K/V
+    of their content lengths) on both sides; each pass is run twice in a row so
+    that the second also reads K/V the first one stored."""
+    dims, tpl, pair, plain, prng = _cfg2_full_depth()
+    curves = []
+
+    def history(fields):
+        for f in fields:
+            n = tpl.content_len[f]
+            shp = (dims.n_layers, dims.n_kv_heads, n, dims.head_dim)
+            Kf, Vf = draw_normal_bf16(prng, shp), draw_normal_bf16(prng, shp)
+            pair.install_slot_kv(0, f, Kf, Vf)
+            s0 = plain.slot_start[f]
+            plain.K[:, 0, :, s0:s0 + n], plain.V[:, 0, :, s0:s0 + n] = Kf, Vf
+            plain.valid_len[0, f] = n
+    history(range(8))
+    last = list(tpl.start_token)
+    for fields, name in (([8, 9, 10], "middle fields 8-10"), ([11], "final field 11")):
+        for off in range(2):
+            ref, worst, e_plain, e_fmt = _both_oracles_step(
+                pair, plain, fields, [off] * len(fields), [last[f] for f in fields],
+                f"cfg2 full depth, {name} at offset {off}", curves)
+            assert worst < ARITH_BOUND, worst
+            assert e_plain < PLAIN_BOUND_CFG2, e_plain
+            for i, f in enumerate(fields):
+                last[f] = int(ref["tok"][i])
+        if fields != [11]:
+            # the middle fields complete (their two decoded tokens stay, data fills the rest)
+            for f in fields:
+                n = tpl.content_len[f] - 2
+                shp = (dims.n_layers, dims.n_kv_heads, n, dims.head_dim)
+                Kf, Vf = draw_normal_bf16(prng, shp), draw_normal_bf16(prng, shp)
+                s0 = plain.slot_start[f] + 2
+                for dec in (pair.dec, plain):
+                    dec.K[:, 0, :, s0:s0 + n], dec.V[:, 0, :, s0:s0 + n] = Kf, Vf
+                    dec.valid_len[0, f] = n + 2
+                for l in range(dims.n_layers):
+                    pair.ctx.kv_append(l, np.ascontiguousarray(np.transpose(Kf[l], (1, 0, 2)), dtype=np.float32),
+                                       np.ascontiguousarray(np.transpose(Vf[l], (1, 0, 2)), dtype=np.float32),
+                                       np.zeros(n, dtype=np.int32), np.arange(s0, s0 + n, dtype=np.int32))
+            pair.ctx.set_valid_len(pair.dec.valid_len)
+    _curve_file("cfg2_later_passes", _curve_lines("workload 2 (28 layers, 7B-class widths), later passes", curves))
     pair.close()
 
 
 def test_workload1_full_depth_schedule_prefix():
     """Workload 1 as benchmarked: all 24 layers at 0.5B-class widths, prefix 1536, the
-    8-field template; the first passes (6 independent fields) and, with shortened
-    contents, the two dependent fields."""
+    8-field template, a whole (shortened) schedule: six passes of the independent
+    fields, then three of the two dependent fields, which read 33 decoded K/V rows
+    of their ancestors.  Against both oracles, layer by layer."""
     dims = model_dims(1)
     tpl = template(1)
     w = draw_weights(1, dims, random_gains=True)
     pair = Pair(dims, tpl, w)
-    _random_prefix_kv(pair, 1)
-    lens = [2, 1, 2, 1, 2, 1, 1, 1]
-    worst, n = run_schedule(pair, lens, tpl.start_token, tag="cfg1 full depth")
-    assert n == 3
-    assert worst < 1e-3, worst
+    plain = O.OracleDecoder(dims, w, tpl.prefix_len, tpl.slot_len, tpl.edges, kv_bf16=False)
+    prng = workload_seed(1, "prefix", 50)
+    shp = (dims.n_layers, dims.n_kv_heads, tpl.prefix_len, dims.head_dim)
+    K, V = draw_normal_bf16(prng, shp), draw_normal_bf16(prng, shp)
+    pair.install_prefix_kv(0, K, V)
+    plain.set_prefix_kv(0, K, V)
+    lens = [6, 5, 6, 5, 6, 5, 3, 3]
+    steps = O.schedule(tpl.n_fields, tpl.edges, lens)
+    assert len(steps) == 9
+    last = list(tpl.start_token)
+    curves = []
+    for si, st in enumerate(steps):
+        bf = [f for f, _ in st]
+        ref, worst, e_plain, e_fmt = _both_oracles_step(pair, plain, bf, [o for _, o in st], [last[f] for f in bf],
+                                                        f"cfg1 full depth, pass {si}: fields {bf}", curves)
+        assert worst < 1e-3, worst
+        assert e_plain < PLAIN_BOUND_CFG1, e_plain
+        for i, f in enumerate(bf):
+            last[f] = int(ref["tok"][i])
+    _curve_file("cfg1_schedule", _curve_lines("workload 1 (24 layers, 0.5B-class widths), whole shortened schedule",
+                                              curves))
     pair.close()
 
 
@@ -432,7 +624,7 @@ def test_the_parity_comparison_notices_a_wrong_oracle(monkeypatch, what, old, ne
             if rest:                                      # then the fields that see them
                 pair.step_both([rest], [[0] * len(rest)], [11] * len(rest), tag=what)
         finally:
-            pair.close()
+            pair.close(need_sure=False)
     run(O)                                                # the oracle as it is: passes
     with pytest.raises(AssertionError):
         run(mutant)

@@ -182,6 +182,90 @@ def test_masked_attention_register_variant_on_small_ragged_shapes(monkeypatch, n
     assert err < 2e-3, err
 
 
+def _wide_slots_template(n_fields=24, slot=64, prefix_len=100, p=0.2, seed=3):
+    """More than 32 tiles past the prefix (24 x 64 = 48 tiles), ragged prefix."""
+    from synth_inputs import Template
+    rng = np.random.default_rng(seed)
+    edges = [(i, j) for j in range(n_fields) for i in range(j) if rng.random() < p]
+    return Template(prefix_len, [slot] * n_fields, edges, [slot] * n_fields, [1] * n_fields, name="wide")
+
+
+@pytest.mark.parametrize("variant", ["0", "1"])
+@pytest.mark.parametrize("B,T", [(1, 1), (2, 2)])
+def test_masked_attention_with_more_than_32_slot_tiles(monkeypatch, variant, B, T):
+    """48 tiles reach past the prefix: more than one workgroup's mask tables hold
+    (32), so the chunks are cut shorter; under both attention kernels."""
+    from paper_2602_02864_amd import fdc_attention_plan
+    monkeypatch.setenv("FDC_ATTN_VARIANT", variant)
+    dims = ATT_DIMS["g4d128"]
+    tpl = _wide_slots_template()
+    plan = fdc_attention_plan(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, tpl.n_fields, T)
+    assert plan["tiles"] - plan["prefix_tiles"] > plan["max_masked_tiles"] and plan["variant"] == int(variant)
+    err = _attention_case(dims, tpl, B, T, seed=11 + B, active_prob=0.9)
+    assert err < 2e-3, err
+
+
+def _tables_case(tpl, B, T, seed, active_prob):
+    """The device's mask words and position table, expanded, against the oracle's
+    dense mask: random cache states, random active subsets and offsets."""
+    from paper_2602_02864_amd import Context
+    dims = ModelDims(1, 64, 1, 1, 64, 32, 8)             # the tables do not depend on the model
+    rng = np.random.default_rng(seed)
+    F, P = tpl.n_fields, tpl.prefix_len
+    ctx = Context(dims, tpl.slot_len, tpl.edges, P, n_scenes=B, max_branches=F, max_tokens=T)
+    n_rows = 0
+    for rep in range(3):
+        valid = np.zeros((B, F), dtype=np.int32)
+        bf = np.full((B, F), -1, dtype=np.int32)
+        bo = np.zeros((B, F), dtype=np.int32)
+        for b in range(B):
+            order = rng.permutation(F)                   # branch entries in any order
+            for i, f in enumerate(order):
+                S = tpl.slot_len[f]
+                valid[b, f] = int(rng.integers(0, S + 1))
+                if S >= T and rng.random() < active_prob:
+                    off = int(rng.integers(0, S - T + 1))
+                    bf[b, i], bo[b, i] = f, off
+                    valid[b, f] = max(valid[b, f], off + T)
+        ctx.set_valid_len(valid)
+        mask, pos = ctx.step_tables_dense(F, T, bf, bo)
+        assert mask.shape == (B * F * T, P + sum(tpl.slot_len))
+        for b in range(B):
+            for r in range(F):
+                m0 = (b * F + r) * T
+                if bf[b, r] < 0:
+                    assert not mask[m0:m0 + T].any() and (pos[m0:m0 + T] == -1).all()
+                    continue
+                want, wpos = O.dense_mask(P, tpl.slot_len, tpl.edges, valid[b], [int(bf[b, r])] * T,
+                                          [int(bo[b, r]) + t for t in range(T)])
+                assert np.array_equal(mask[m0:m0 + T].astype(bool), want), (rep, b, r)
+                assert np.array_equal(pos[m0:m0 + T], wpos), (rep, b, r)
+                n_rows += T
+    ctx.close()
+    return n_rows
+
+
+@pytest.mark.parametrize("T", [1, 4])
+@pytest.mark.parametrize("cfg_id,B,kw", [(0, 1, {}), (1, 2, {}), (2, 1, {}), (3, 3, {"rho": 0.3}), (3, 2, {"rho": 1.0}),
+                                         (4, 8, {})])
+def test_device_mask_and_positions_are_bit_exact_on_the_workload_templates(cfg_id, B, kw, T):
+    """Eq. 1 / Sec. 3.3 on the device: what the kernels consume (one visibility word
+    per row and 32-key tile past the prefix, one position id per row) expanded to
+    a dense mask equals the oracle's, for the five workload templates, one and
+    four tokens per branch, inactive entries included."""
+    assert _tables_case(template(cfg_id, **kw), B, T, 100 * cfg_id + T, 0.7) > 0
+
+
+@pytest.mark.parametrize("seed,F,P,max_slot,p,B,T", [(1, 7, 37, 9, 0.3, 2, 1), (3, 5, 0, 20, 0.6, 2, 4),
+                                                     (8, 40, 64, 6, 0.1, 1, 1), (12, 64, 1, 5, 0.05, 3, 2),
+                                                     (13, 9, 95, 70, 0.5, 2, 4)])
+def test_device_mask_and_positions_are_bit_exact_on_ragged_templates(seed, F, P, max_slot, p, B, T):
+    tpl = random_dag_template(500 + seed, F, P, max_slot, p, 100)
+    tpl.slot_len = [max(s, T) for s in tpl.slot_len]
+    assert _tables_case(tpl, B, T, seed, 0.6) > 0
+    assert _tables_case(_wide_slots_template(), 2, T, seed, 0.8) > 0
+
+
 def test_masked_attention_microbenchmark_shape_sampled():
     """Workload 3 geometry (16 fields x 64 slots, prefix 4096, 32/8 heads, D 128)
     at 2 scenes: every branch active at offset 32, all other slots full."""

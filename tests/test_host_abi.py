@@ -261,3 +261,190 @@ def test_null_pointers_are_rejected_not_dereferenced():
     assert L.fdc_sched_peek(None, 1, None, None, None) == fb.FDC_EINVAL
     assert L.fdc_sched_advance(None, 0, None) == fb.FDC_EINVAL
     assert L.fdc_packed_weight_bytes(16, 32) == 1024 and L.fdc_packed_weight_bytes(1000, 32) == 1008 * 64
+
+
+def _check_plan(dims, tpl, B, R, T, tag):
+    """What the attention kernels assume of a context's launch plan: the chunks
+    tile the key range, none exceeds the kernel's tile list, none has more tiles
+    past the prefix than the mask tables hold, and a chunk's real tiles never
+    outnumber its weighted size (the register kernel lists `cb` candidates)."""
+    from paper_2602_02864_amd import fdc_attention_plan
+    p = fdc_attention_plan(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T)
+    first = p["chunk_first_tile"]
+    N = tpl.prefix_len + sum(tpl.slot_len)
+    assert p["tiles"] == (N + 31) // 32 and p["prefix_tiles"] == tpl.prefix_len // 32, tag
+    assert len(first) == p["chunks"] + 1 and first[0] == 0 and first[-1] == p["tiles"], (tag, p)
+    assert p["wq"] >= 4 and p["nrt"] in (1, 2) and p["rg_max"] >= 1, (tag, p)
+    rows = R * T * (dims.n_q_heads // dims.n_kv_heads)
+    assert p["rg_max"] * p["nrt"] * 32 >= rows, (tag, p)
+    for c in range(p["chunks"]):
+        n = first[c + 1] - first[c]
+        assert 0 <= n <= p["max_chunk_tiles"] and n <= p["cb"], (tag, c, p)
+        masked = max(0, first[c + 1] - max(first[c], p["prefix_tiles"]))
+        assert masked <= p["max_masked_tiles"], (tag, c, p)
+        if p["variant"] == 0:
+            assert (n + 1) // 2 <= 64, (tag, c, p)        # one tile per lane and stream
+    return p
+
+
+def test_attention_plan_bounds_over_the_admissible_shapes(monkeypatch):
+    """plan_attention at the corners: few and many fields, short and long slots,
+    no prefix and a long one, one scene and many, the row limit, both kernels."""
+    from synth_inputs import ModelDims, Template
+    seen = set()
+    shapes = []
+    for F, S in [(1, 1), (1, 2048), (3, 5), (12, 64), (16, 64), (24, 64), (32, 32), (64, 1), (64, 31), (64, 96),
+                 (40, 200), (64, 512)]:
+        for P in (0, 1, 31, 32, 100, 3072, 8192, 70000):
+            shapes.append((F, S, P))
+    for variant in (None, "0", "1"):
+        if variant is None:
+            monkeypatch.delenv("FDC_ATTN_VARIANT", raising=False)
+        else:
+            monkeypatch.setenv("FDC_ATTN_VARIANT", variant)
+        for (F, S, P) in shapes:
+            tpl = Template(P, [S] * F, [(i, i + 1) for i in range(F - 1)], [S] * F, [0] * F)
+            for Hq, Hkv, D in [(4, 4, 64), (14, 2, 64), (28, 4, 128), (32, 8, 128)]:
+                dims = ModelDims(1, 256, Hq, Hkv, D, 512, 1000)
+                for B, R, T in [(1, 1, 1), (1, F, 1), (16, min(F, 16), 1), (8, min(F, 32), 4), (1, 1, min(S, 1024)),
+                                (2, min(F, 8), min(S, 64))]:
+                    if B * R * T > 1024 or T > S:
+                        continue
+                    p = _check_plan(dims, tpl, B, R, T, (variant, F, S, P, Hq, Hkv, D, B, R, T))
+                    seen.add((p["variant"], p["chunks"] > 1, p["tiles"] - p["prefix_tiles"] > p["max_masked_tiles"]))
+    assert len(seen) >= 6          # both kernels, one and several chunks, few and many slot tiles
+    # the five workloads as benchmarked
+    from synth_inputs import model_dims
+    for cfg, B, R, T in [(0, 1, 3, 1), (1, 1, 6, 1), (2, 1, 8, 1), (3, 16, 16, 1), (4, 8, 8, 4), (4, 8, 32, 4)]:
+        t = template(cfg)
+        _check_plan(model_dims(cfg), t, B, R, T, f"cfg{cfg}")
+
+
+def test_create_refuses_more_cache_positions_than_the_kernels_index():
+    """Tile numbers travel as 16-bit values in the attention kernels: a context
+    with more than 65535 tiles of 32 positions is refused (and one just below is
+    accepted; nothing is allocated at creation)."""
+    import ctypes as C
+    from synth_inputs import ModelDims
+    dims = ModelDims(1, 64, 1, 1, 64, 32, 8)
+    desc = fb.ModelDesc(dims.n_layers, dims.d_model, dims.n_q_heads, dims.n_kv_heads, dims.head_dim,
+                        dims.d_mlp, dims.vocab, dims.rope_base, dims.norm_eps)
+    sl = np.array([32], dtype=np.int32)
+    for P, want in [(65534 * 32, fb.FDC_OK), (65535 * 32, fb.FDC_ECAP)]:
+        h = C.c_void_p()
+        rc = fb.lib().fdc_create(C.byref(desc), 1, fb._p(sl), 0, None, None, P, 1, 1, 1, C.byref(h))
+        assert rc == want, (P, rc)
+        if rc == fb.FDC_OK:
+            fb.lib().fdc_destroy(h)
+
+
+def test_linear_static_refuses_oversize_before_touching_the_gpu():
+    """The entry point that allocates nothing checks its size limit on the host."""
+    import ctypes as C
+    buf = (C.c_float * 64)()
+    a = C.addressof(buf)
+    a += (-a) % 16
+    rc = fb.lib().fdc_linear_static(a, a, a, 256, 37888, 3584, None)
+    assert rc == fb.FDC_ECAP and b"static" in fb.lib().fdc_last_error()
+
+
+_SAN_DRIVER = r"""
+// Drives every host-only entry point over enumerated and pseudo-random inputs
+// (valid and invalid) and prints a hash of everything that came back.  Built
+// with AddressSanitizer and UndefinedBehaviorSanitizer: a bad access aborts.
+#include <cstdio>
+#include <cstdint>
+#include <vector>
+#include "fdc.h"
+static uint64_t H = 1469598103934665603ULL;
+static void mix(int64_t v) { for (int i = 0; i < 8; ++i) { H ^= (uint64_t)(v >> (8 * i)) & 0xff; H *= 1099511628211ULL; } }
+static uint64_t S = 88172645463325252ULL;
+static uint32_t rnd(uint32_t n) { S = S * 6364136223846793005ULL + 1442695040888963407ULL; return (uint32_t)((S >> 33) % n); }
+int main() {
+    for (int it = 0; it < 400; ++it) {
+        const int F = 1 + (int)rnd(it < 200 ? 6 : 130);
+        std::vector<int32_t> slot(F), src, dst, start(F), level(F), valid(F);
+        for (int f = 0; f < F; ++f) slot[f] = 1 + (int)rnd(9);
+        const int E = (int)rnd(3 * F + 1);
+        for (int e = 0; e < E; ++e) {
+            int u = (int)rnd(F), v = (int)rnd(F);
+            if (rnd(8) != 0 && u > v) { int t = u; u = v; v = t; }      // mostly forward edges
+            if (rnd(40) == 0) v = F + (int)rnd(3);                      // sometimes out of range
+            src.push_back(u); dst.push_back(v);
+        }
+        const int W = (F + 63) / 64, P = (int)rnd(70);
+        std::vector<uint64_t> anc((size_t)F * W);
+        int32_t total = -1;
+        int32_t rc = fdc_build_mask(F, slot.data(), E, src.data(), dst.data(), P, anc.data(), start.data(),
+                                    level.data(), &total);
+        mix(rc);
+        if (rc != FDC_OK) { mix(fdc_last_error()[0] != 0); continue; }
+        for (auto a : anc) mix((int64_t)a);
+        for (int f = 0; f < F; ++f) { mix(start[f]); mix(level[f]); }
+        mix(total);
+        // dense mask of a few rows under a random cache state
+        const int nr = 1 + (int)rnd(5);
+        std::vector<int32_t> rf(nr), ro(nr), pos(nr);
+        for (int f = 0; f < F; ++f) valid[f] = (int)rnd(slot[f] + 1);
+        for (int r = 0; r < nr; ++r) { rf[r] = (int)rnd(F); ro[r] = (int)rnd(slot[rf[r]]); }
+        if (rnd(25) == 0) ro[0] = slot[rf[0]];                           // an offset past the slot
+        std::vector<uint8_t> mask((size_t)nr * total);
+        rc = fdc_dense_mask(F, slot.data(), start.data(), anc.data(), P, valid.data(), nr, rf.data(), ro.data(),
+                            mask.data(), pos.data());
+        mix(rc);
+        if (rc == FDC_OK) { for (auto m : mask) mix(m); for (auto p : pos) mix(p); }
+        // Algorithm 1 to the end with drawn content lengths, through peek / advance
+        std::vector<int32_t> len(F), bf(F), bo(F), fin(F), done(F, 0);
+        for (int f = 0; f < F; ++f) len[f] = 1 + (int)rnd(slot[f]);
+        fdc_sched* sc = nullptr;
+        rc = fdc_sched_create(F, E, src.data(), dst.data(), rnd(2) ? len.data() : nullptr, &sc);
+        mix(rc);
+        if (rc != FDC_OK) continue;
+        for (int guard = 0; guard < 100000; ++guard) {
+            int32_t n = 0;
+            rc = fdc_sched_peek(sc, F, bf.data(), bo.data(), &n);
+            mix(rc); mix(n);
+            if (rc != FDC_OK || n == 0) break;
+            for (int i = 0; i < n; ++i) { mix(bf[i]); mix(bo[i]); done[bf[i]]++; fin[i] = done[bf[i]] >= len[bf[i]]; }
+            mix(fdc_sched_advance(sc, n, fin.data()));
+        }
+        mix(fdc_sched_advance(sc, 3, fin.data()));                       // wrong count: an error, not a fault
+        mix(fdc_sched_complete(sc, F, 1));                               // field out of range
+        int64_t ps = 0, tk = 0; int32_t un = 0;
+        mix(fdc_sched_stats(sc, &ps, &tk, &un)); mix(ps); mix(tk); mix(un);
+        fdc_sched_destroy(sc);
+    }
+    mix(fdc_build_mask(0, nullptr, 0, nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr));
+    printf("%llu\n", (unsigned long long)H);
+    return 0;
+}
+"""
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """fdc_host.cpp (everything of the library that runs without a GPU) built with
+    -fsanitize=address,undefined and driven over valid and invalid inputs; the same
+    program built without sanitizers against the regular library must print the
+    same hash, so the sanitized run did exercise the shipped code's behaviour."""
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no C++ compiler")
+    src = tmp_path / "drive_host.cpp"
+    src.write_text(_SAN_DRIVER)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2602_02864_amd", "csrc")]
+    host = os.path.join(ROOT, "paper_2602_02864_amd", "csrc", "fdc_host.cpp")
+    san = tmp_path / "drive_san"
+    subprocess.run([gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-static-libasan", "-static-libubsan", *inc, str(src), host, "-o", str(san)], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([str(san)], capture_output=True, text=True, env=env)
+    assert r.returncode == 0, r.stderr[-3000:]
+    plain = tmp_path / "drive_plain"
+    libdir = os.path.dirname(fb.LIB_PATH)
+    subprocess.run([gxx, "-std=c++17", "-O1", *inc, str(src), "-o", str(plain), "-L", libdir, "-lfdc",
+                    "-Wl,-rpath," + libdir], check=True)
+    r2 = subprocess.run([str(plain)], capture_output=True, text=True)
+    assert r2.returncode == 0, r2.stderr[-3000:]
+    assert r.stdout.strip() == r2.stdout.strip() and int(r.stdout) != 0
