@@ -171,10 +171,12 @@ int32_t fdc_pack_weight(const void* src_dev, void* dst_dev, int64_t n_out, int64
  * fdc_build_mask.  n_scenes = B; max_branches = largest R and max_tokens =
  * largest T a step will use.
  * Tuning and test hooks read from the environment at creation: FDC_ATTN_VARIANT
- * (0 / 1: attention kernel with K/V tiles shared through LDS / kept in
- * registers; default by cache size) and FDC_ATTN_WGS (workgroups the key chunks
- * of one attention launch are cut for).  Results do not depend on them beyond
- * the order of floating-point sums.
+ * (0 / 1 / 2: attention kernel with K/V tiles shared through LDS by the two row
+ * tiles of a KV head / kept in registers / shared through LDS by up to eight
+ * row tiles; default: 2 when a step can have more than 64 rows per KV head,
+ * else by cache size) and FDC_ATTN_WGS (workgroups the key chunks of one
+ * attention launch are cut for).  Results do not depend on them beyond the
+ * order of floating-point sums.
  */
 int32_t fdc_create(const fdc_model_desc* model,
                    int32_t n_fields, const int32_t* slot_len,

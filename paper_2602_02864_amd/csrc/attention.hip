@@ -214,6 +214,32 @@ __device__ __forceinline__ void build_tables(const AttnArgs& a, const StepMeta& 
     __syncthreads();
 }
 
+// The same tables without the per-branch staging array: every (tile, row) entry
+// fetches its word itself (rows of one branch token read the same address).
+template <int NR, int NT>
+__device__ __forceinline__ void build_tables_direct(const AttnArgs& a, const StepMeta& sm, int b, int kvh, int rg,
+                                                    int mt0, int nmt, int* row_m, int* row_head,
+                                                    uint32_t (*rowmask)[NR], uint32_t* tile_any) {
+    const int tid = threadIdx.x;
+    const int RT = sm.R * sm.T;
+    const uint32_t* __restrict__ words = a.mask_words + ((size_t)b * a.mw_tiles + (mt0 - (a.P >> 5))) * RT;
+    for (int t = tid; t < nmt; t += NT) tile_any[t] = 0u;
+    for (int r = tid; r < NR; r += NT) {
+        const RowInfo ri = row_info(rg * NR + r, b, kvh, a.G, sm);
+        row_m[r] = ri.m;
+        row_head[r] = ri.head;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < nmt * NR; idx += NT) {
+        const int t = idx / NR, r = idx % NR;
+        const int jr = (rg * NR + r) / a.G;
+        const uint32_t bits = (row_m[r] >= 0 && jr < RT) ? words[(size_t)t * RT + jr] : 0u;
+        rowmask[t][r] = bits;
+        if (bits) atomicOr(&tile_any[t], bits);
+    }
+    __syncthreads();
+}
+
 template <int D, int NRT, bool QF32>
 __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnArgs a, StepMeta sm) {
     constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, NT = kStreams * NRT * 64;
@@ -484,6 +510,301 @@ __global__ __launch_bounds__(kStreams* NRT * 64) void attn_partial_kernel(AttnAr
             ml[0] = mg;
             ml[1] = l_run * e0 + l1 * e1;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Wide variant, for steps with many rows per KV head (several scenes' worth of
+// branches x tokens x group heads: up to NRT * 32 = 256 rows).  One workgroup of
+// NRT wavefronts - two per SIMD at NRT = 8 - takes ALL row tiles of one (scene,
+// KV head, key chunk): every K/V tile is fetched from memory once (direct-to-LDS
+// ring, as above) and read from LDS by all wavefronts, one row tile each.  With
+// two wavefronts on a SIMD the matrix instructions of one run under the softmax
+// arithmetic of the other.  A wavefront keeps 32 rows: queries (bf16 head + tail)
+// and the output accumulators in registers, K and V fragments pass through one
+// set of registers (K first, V re-uses them).  One tile stream per workgroup; a
+// chunk holds at most 64 tiles (one per lane of the tile list).
+template <int D, int NRT, bool QF32>
+__global__ __launch_bounds__(NRT * 64, 2) void attn_partial_wide_kernel(AttnArgs a, StepMeta sm) {
+    constexpr int DJ = D / 16, DT = D / 32, NR = NRT * 32, NT = NRT * 64;
+    // TPI tiles are consumed between two barriers (with eight wavefronts two: half
+    // as many barriers, and between them the wavefronts drift apart, so that on a
+    // SIMD the matrix instructions of one run under the softmax arithmetic of the
+    // other and the LDS reads spread out).  Ring: the TPI tiles being consumed plus
+    // kDist tiles requested ahead.  Four wavefronts: three stages, so that two
+    // workgroups share a compute unit's LDS.
+    constexpr int TPI = NRT >= 8 ? 2 : 1;
+    constexpr int kDist = NRT >= 8 ? 4 : 2;         // tiles in flight while a group is consumed (multiple of TPI)
+    constexpr int kWideStages = TPI + kDist;
+    constexpr int TILE = 32 * D;
+    constexpr int LPT = 2 * DJ;                     // 1 KiB load instructions per K+V tile
+    static_assert(LPT % NRT == 0 || NRT > LPT, "tile pieces must divide over the wavefronts");
+    constexpr int LPW = LPT >= NRT ? LPT / NRT : 1; // pieces issued by each (issuing) wavefront
+    constexpr int NISS = LPT >= NRT ? NRT : LPT;    // wavefronts that issue copies
+    __shared__ __attribute__((aligned(16))) uint16_t stage[kWideStages][2 * TILE];
+    __shared__ uint32_t rowmask[kMaxMaskedTiles][NR];
+    __shared__ uint32_t tile_any[kMaxMaskedTiles];
+    __shared__ int row_m[NR], row_head[NR];
+    __shared__ uint16_t act_list[kMaxChunkTilesWide];
+    __shared__ int n_act_sh;
+
+    // Row groups of one (scene, KV head, chunk) read the same tiles: consecutive
+    // ids on one compute die (launch ids go round the eight dies)
+    const int n_wg = gridDim.x * gridDim.y * gridDim.z;
+    int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    if ((n_wg & 7) == 0) lin = (lin & 7) * (n_wg >> 3) + (lin >> 3);
+    const int rg = lin % a.n_rg, chunk = (lin / a.n_rg) % a.n_chunks, z = lin / (a.n_rg * a.n_chunks);
+    const int b = z / a.Hkv, kvh = z % a.Hkv;
+    // the wavefront's index as a scalar: tile piece numbers and copy addresses then
+    // live in scalar registers
+    const int tid = threadIdx.x, rt = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int r32 = lane & 31, hh = lane >> 5;
+    const int cb0 = chunk_start(a, chunk), blk_end = min(a.NB, chunk_start(a, chunk + 1));
+    const int mt0 = max(cb0, a.P >> 5);
+    const int nmt = max(0, blk_end - mt0);
+
+    // The query rows are requested first: where a row of the group lives (step row
+    // m, head) follows from the launch shape alone; whether its branch is active is
+    // known only after the tables and decides below if it is used.
+    f32x4 qraw[QF32 ? DJ : 1][2];
+    bf16x8 qb[QF32 ? 1 : DJ];
+    {
+        const int gr = rg * NR + rt * 32 + r32;
+        const int jr = gr / a.G, ridx = jr / sm.T;
+        const bool exists = ridx < sm.R;
+        const int m = exists ? (b * sm.R + ridx) * sm.T + jr % sm.T : 0;
+        const size_t qo = ((size_t)m * a.Hq + kvh * a.G + gr % a.G) * D + 8 * hh;
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) {
+            if (QF32) {
+                qraw[j][0] = qraw[j][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (exists) {
+                    qraw[j][0] = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 16 * j);
+                    qraw[j][1] = *reinterpret_cast<const f32x4*>(a.q_f32 + qo + 16 * j + 4);
+                }
+            } else {
+                qb[j] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                if (exists) qb[j] = *reinterpret_cast<const bf16x8*>(a.q_bf16 + qo + 16 * j);
+            }
+        }
+    }
+
+    build_tables_direct<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, rowmask, tile_any);
+    if (rt == 0) {
+        const int blk = cb0 + lane;                         // at most 64 tiles per chunk
+        bool actv = blk < blk_end;
+        if (actv && blk >= mt0) actv = tile_any[blk - mt0] != 0u;
+        const unsigned long long mask = __ballot(actv);
+        if (actv) act_list[__popcll(mask & ((1ull << lane) - 1ull))] = (uint16_t)blk;
+        if (lane == 0) n_act_sh = __popcll(mask);
+    }
+    __syncthreads();
+    const int n_act = n_act_sh;
+    const int my_tiles = lane < n_act ? (int)act_list[lane] : 0;
+
+    // query operand (bf16 head + tail), zero for rows of inactive branches; the
+    // loads have landed while the tables were built
+    Frag qh[DJ], ql[QF32 ? DJ : 1];
+    const bool row_act = row_m[rt * 32 + r32] >= 0;
+    // a wavefront none of whose rows is active still copies its share of the tiles
+    // and meets the barriers, but does no arithmetic
+    const bool wave_act = __any(row_act);
+#pragma unroll
+    for (int j = 0; j < DJ; ++j) {
+        if (QF32) {
+            const f32x4 zz = {0.f, 0.f, 0.f, 0.f};
+            const f32x4 q0 = row_act ? qraw[j][0] : zz, q1 = row_act ? qraw[j][1] : zz;
+            split2(q0[0], q0[1], qh[j].u[0], ql[j].u[0]);
+            split2(q0[2], q0[3], qh[j].u[1], ql[j].u[1]);
+            split2(q1[0], q1[1], qh[j].u[2], ql[j].u[2]);
+            split2(q1[2], q1[3], qh[j].u[3], ql[j].u[3]);
+        } else {
+            qh[j].v = row_act ? qb[j] : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
+    // no load of the set-up may be counted among the tile copies below
+    __builtin_amdgcn_s_waitcnt(0);
+
+    const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
+    const uint32_t lane_off = (uint32_t)lane * 8;           // bf16 elements
+    auto issue = [&](int i, int stg) {
+        if (i >= n_act || rt >= NISS) return;
+        const int blk = __builtin_amdgcn_readlane(my_tiles, i);
+        const size_t toff = (tile_base + blk) * TILE;       // scalar
+#pragma unroll
+        for (int p = 0; p < LPW; ++p) {
+            const int piece = rt * LPW + p;                 // < DJ: K, else V (scalar)
+            const uint16_t* base = (piece < DJ ? a.kc : a.vc) + toff + (piece % DJ) * 512;
+            uint16_t* dst = &stage[stg][piece * 512];
+            __builtin_amdgcn_global_load_lds((glb_void*)(base + lane_off), (lds_void*)dst, 16, 0, 2 /* nt: streamed once */);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < kDist; ++i) issue(i, i);
+
+    f32x16 o[DT];
+    float m_run = kMaxFloor, l_run = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+
+    const uint32_t stage_off = lds_off(&stage[0][0]) + lane * 16;
+    const uint32_t rowmask_off = lds_off(&rowmask[0][rt * 32 + r32]);
+    const uint32_t any_off = lds_off(&tile_any[0]);
+    // One 32-key tile against this wavefront's 32 rows, in two phases: scores
+    // (S^T = K * Q^T into `sc`), then softmax and O^T += V^T * P^T.  The eight
+    // fragments of K and then the eight of V pass through the same registers.
+    // Two independent accumulators (query heads, query tails), so that consecutive
+    // matrix instructions never wait for each other's result; summed afterwards.
+    f32x16 sc;
+    auto scores = [&](int stg) {
+        const uint32_t ks = stage_off + stg * (4 * TILE);   // bytes
+        Frag fr[DJ];
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) lds_read128(fr[j], ks + j * 1024);
+        f32x16 st;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) sc[k] = st[k] = 0.f;
+        constexpr int HJ = DJ / 2;
+        asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(HJ) : "memory");
+#pragma unroll
+        for (int j = 0; j < HJ; ++j) {
+            asm volatile("" : "+v"(fr[j].v));
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, qh[j].v, sc, 0, 0, 0);
+            if (QF32) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, ql[j].v, st, 0, 0, 0);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = HJ; j < DJ; ++j) {
+            asm volatile("" : "+v"(fr[j].v));
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, qh[j].v, sc, 0, 0, 0);
+            if (QF32) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, ql[j].v, st, 0, 0, 0);
+        }
+        if (QF32) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) sc[k] += st[k];
+        }
+    };
+    auto softmax_pv = [&](int stg, int blk) {
+        const bool masked = blk >= mt0;                     // the tile reaches into the slots
+        const uint32_t vs = stage_off + stg * (4 * TILE) + 2 * TILE;
+        uint32_t vbits = 0xffffu, anyb = 0xffffu;
+        bool holes = false;                                 // some key of the tile is seen by no row
+        // the V fragments are requested now and consumed after the softmax:
+        // fragment dt*2 + s2 of the V half of the stage
+        Frag fr[DJ];
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) lds_read128(fr[j], vs + j * 1024);
+        if (masked) {
+            uint32_t w0 = lds_read32(rowmask_off + (blk - mt0) * (NR * 4));
+            uint32_t w1 = lds_read32(any_off + (blk - mt0) * 4);
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w0), "+v"(w1)::"memory");
+            vbits = lane_bits(w0, hh);
+            anyb = lane_bits(w1, hh);
+            holes = __builtin_amdgcn_readfirstlane(w1) != 0xffffffffu;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) sc[k] = keep_if(sc[k], vbits, k);
+        }
+        float mx = kNegBig;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) mx = fmaxf(mx, sc[k]);
+        mx = fmaxf(mx, other_half(mx, hh));
+        const float m_new = fmaxf(m_run, mx * a.scale_log2);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+        Frag ph[2], pl[2];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[8 * s2 + 2 * k], a.scale_log2, -m_new));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[8 * s2 + 2 * k + 1], a.scale_log2, -m_new));
+                psum += p0 + p1;
+                split2(p0, p1, ph[s2].u[k], pl[s2].u[k]);
+            }
+        l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) o[dt][k] *= alpha;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) asm volatile("" : "+v"(fr[j].v));
+        if (holes) {
+            // keys nobody sees may be padding or not yet written: zeroed so that 0 * garbage stays 0
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t wm = ((anyb >> (8 * s2 + 2 * k) & 1u) ? 0x0000ffffu : 0u) |
+                                        ((anyb >> (8 * s2 + 2 * k + 1) & 1u) ? 0xffff0000u : 0u);
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) fr[dt * 2 + s2].u[k] &= wm;
+                }
+        }
+        // round the four output blocks: consecutive matrix instructions are independent
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[dt * 2 + s2].v, ph[s2].v, o[dt], 0, 0, 0);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[dt * 2 + s2].v, pl[s2].v, o[dt], 0, 0, 0);
+        }
+    };
+
+    // Main loop: groups of TPI tiles.  Barrier g: every copy of the tiles of group g
+    // has landed, and nobody reads the tiles of group g - 1 any more; their stages
+    // take the copies of the group kDist tiles ahead.
+    int stg = 0;
+    for (int i0 = 0; i0 < n_act; i0 += TPI) {
+        if (rt < NISS) {
+            // my copies of the group have landed; later groups stay in flight
+            const int later = min(n_act - (i0 + TPI), kDist - TPI);
+            if (later >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPW) : "memory");
+            else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+        for (int t = 0; t < TPI; ++t) {
+            int into = stg + t + kDist;
+            if (into >= kWideStages) into -= kWideStages;
+            issue(i0 + t + kDist, into);
+        }
+#pragma unroll
+        for (int t = 0; t < TPI; ++t) {
+            if (i0 + t < n_act && wave_act) {
+                int st = stg + t;
+                if (st >= kWideStages) st -= kWideStages;
+                scores(st);
+                softmax_pv(st, __builtin_amdgcn_readlane(my_tiles, i0 + t));
+            }
+        }
+        stg += TPI;
+        if (stg >= kWideStages) stg -= kWideStages;
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+
+    // ---- emit the chunk's partial: every wavefront its own row tile ---------------
+    l_run += other_half(l_run, hh);
+    const size_t pidx = ((size_t)z * a.n_rg + rg) * a.n_chunks + chunk;
+    f32x4* po = reinterpret_cast<f32x4*>(a.part_o) + pidx * (NRT * DT * 4 * 64);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+            po[((rt * DT + dt) * 4 + i4) * 64 + lane] =
+                f32x4{o[dt][4 * i4], o[dt][4 * i4 + 1], o[dt][4 * i4 + 2], o[dt][4 * i4 + 3]};
+    if (hh == 0) {
+        float* ml = a.part_ml + (pidx * NR + rt * 32 + r32) * 2;
+        ml[0] = m_run;
+        ml[1] = l_run;
     }
 }
 
@@ -807,13 +1128,20 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm
 template <int D, int NRT>
 void launch_t(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
     const int z = sm.B * a.Hkv;
-    const dim3 grid(a.n_chunks, a.n_rg, z), block(kStreams * NRT * 64);
-    if (a.variant == 1) {
-        if (a.q_f32) hipLaunchKernelGGL((attn_partial_reg_kernel<D, NRT, true>), grid, dim3(256), 0, st, a, sm);
-        else hipLaunchKernelGGL((attn_partial_reg_kernel<D, NRT, false>), grid, dim3(256), 0, st, a, sm);
+    const dim3 grid(a.n_chunks, a.n_rg, z);
+    if constexpr (NRT >= 4) {
+        // only the wide kernel has that many row tiles per workgroup
+        if (a.q_f32) hipLaunchKernelGGL((attn_partial_wide_kernel<D, NRT, true>), grid, dim3(NRT * 64), 0, st, a, sm);
+        else hipLaunchKernelGGL((attn_partial_wide_kernel<D, NRT, false>), grid, dim3(NRT * 64), 0, st, a, sm);
     } else {
-        if (a.q_f32) hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), grid, block, 0, st, a, sm);
-        else hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), grid, block, 0, st, a, sm);
+        const dim3 block(kStreams * NRT * 64);
+        if (a.variant == 1) {
+            if (a.q_f32) hipLaunchKernelGGL((attn_partial_reg_kernel<D, NRT, true>), grid, dim3(256), 0, st, a, sm);
+            else hipLaunchKernelGGL((attn_partial_reg_kernel<D, NRT, false>), grid, dim3(256), 0, st, a, sm);
+        } else {
+            if (a.q_f32) hipLaunchKernelGGL((attn_partial_kernel<D, NRT, true>), grid, block, 0, st, a, sm);
+            else hipLaunchKernelGGL((attn_partial_kernel<D, NRT, false>), grid, block, 0, st, a, sm);
+        }
     }
     constexpr int Q4 = NRT * (D / 32) * 4 * 64;
     // one wavefront per workgroup: the partials of a row group come in through as
@@ -837,10 +1165,14 @@ void launch_mask_words(const StepMeta& sm, const uint64_t* anc, int P, int n_til
 
 void launch_attention(const AttnArgs& a, const StepMeta& sm, hipStream_t st) {
     if (a.D == 128) {
-        if (a.nrt == 2) launch_t<128, 2>(a, sm, st);
+        if (a.nrt == 8) launch_t<128, 8>(a, sm, st);
+        else if (a.nrt == 4) launch_t<128, 4>(a, sm, st);
+        else if (a.nrt == 2) launch_t<128, 2>(a, sm, st);
         else launch_t<128, 1>(a, sm, st);
     } else {
-        if (a.nrt == 2) launch_t<64, 2>(a, sm, st);
+        if (a.nrt == 8) launch_t<64, 8>(a, sm, st);
+        else if (a.nrt == 4) launch_t<64, 4>(a, sm, st);
+        else if (a.nrt == 2) launch_t<64, 2>(a, sm, st);
         else launch_t<64, 1>(a, sm, st);
     }
 }

@@ -109,6 +109,33 @@ namespace {
 void plan_attention(fdc_ctx* c) {
     const int G = c->m.n_q_heads / c->m.n_kv_heads;
     const int rows = c->Rmax * c->Tmax * G;
+    int forced = -1;
+    if (const char* e = std::getenv("FDC_ATTN_VARIANT")) forced = std::atoi(e);
+    const long t0 = c->P / 32, masked_total = c->NB - t0;
+    // More than 64 rows per KV head (several tokens per branch, many branches): one
+    // workgroup of 4 or 8 wavefronts takes up to 128 / 256 rows of a KV head, so a
+    // K/V tile is fetched once for all of them and shared through LDS.
+    if (forced == 2 || (forced < 0 && rows > 64)) {
+        c->attn_variant = 2;
+        c->attn_nrt = rows > 128 ? 8 : 4;
+        const int NR = c->attn_nrt * 32;
+        c->attn_rg_max = (rows + NR - 1) / NR;
+        // tiles past the prefix carry masks and measure about 1.5 plain tiles each:
+        // chunks are cut equal in weighted tiles, or the chunk with the slots would
+        // finish long after the others
+        c->attn_wq = 6;
+        const long total = t0 + (masked_total * c->attn_wq + 3) / 4;
+        const long zr = (long)c->B * c->m.n_kv_heads * c->attn_rg_max;
+        long want_wgs = c->attn_nrt == 8 ? 256 : 512;      // four-wavefront workgroups run two to a compute unit
+        if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
+        const long chunks = std::max(1L, (want_wgs + zr / 2) / zr);
+        long cb = (total + chunks - 1) / chunks;
+        cb = std::min(std::max(4L, cb), (long)kMaxChunkTilesWide);
+        if (masked_total > kMaxMaskedTiles) cb = std::min(cb, (long)kMaxMaskedTiles);
+        c->attn_cb = (int)cb;
+        c->attn_chunks = (int)((total + cb - 1) / cb);
+        return;
+    }
     c->attn_nrt = rows > 32 ? 2 : 1;
     const int NR = c->attn_nrt * 32;
     c->attn_rg_max = (rows + NR - 1) / NR;
@@ -122,8 +149,7 @@ void plan_attention(fdc_ctx* c) {
     c->attn_variant = large ? 1 : 0;
     long want_wgs = (large ? 256L : 128L) * (c->m.head_dim == 128 ? 1 : 2);
     if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
-    if (const char* e = std::getenv("FDC_ATTN_VARIANT")) c->attn_variant = std::atoi(e) == 1 ? 1 : 0;
-    const long t0 = c->P / 32, masked_total = c->NB - t0;
+    if (forced == 0 || forced == 1) c->attn_variant = forced;
     long cb, total = c->NB;
     if (c->attn_variant == 1 && !std::getenv("FDC_ATTN_WGS")) {
         // Tiles past the prefix carry masks and measure about 1.5 plain tiles
@@ -622,7 +648,7 @@ int32_t fdc_attention_plan(const fdc_ctx* c, int32_t* info, int32_t* chunk_first
     info[5] = c->attn_wq;
     info[6] = c->NB;
     info[7] = c->P / 32;
-    info[8] = c->attn_variant == 1 ? kMaxChunkTilesReg : kMaxChunkTiles;
+    info[8] = c->attn_variant == 2 ? kMaxChunkTilesWide : c->attn_variant == 1 ? kMaxChunkTilesReg : kMaxChunkTiles;
     info[9] = kMaxMaskedTiles;
     if (chunk_first_tile)
         for (int ch = 0; ch <= c->attn_chunks; ++ch)

@@ -20,6 +20,7 @@ constexpr int kMaxRowsStep = 1024;  // rows per step overall
 constexpr int kStageSlots = 8;      // pinned staging ring for per-step metadata
 constexpr int kMaxChunkTiles = 128; // 32-key tiles one attention workgroup walks at most (LDS-shared tiles)
 constexpr int kMaxChunkTilesReg = 512;  // ... with tiles in registers
+constexpr int kMaxChunkTilesWide = 64;  // ... in the many-row kernel (one tile list entry per lane)
 constexpr int kMaxMaskedTiles = 32; // ... of which this many may reach into the slots
 
 // How one projection y = x W^T is cut: S splits of the reduction dimension,

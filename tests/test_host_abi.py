@@ -274,7 +274,7 @@ def _check_plan(dims, tpl, B, R, T, tag):
     N = tpl.prefix_len + sum(tpl.slot_len)
     assert p["tiles"] == (N + 31) // 32 and p["prefix_tiles"] == tpl.prefix_len // 32, tag
     assert len(first) == p["chunks"] + 1 and first[0] == 0 and first[-1] == p["tiles"], (tag, p)
-    assert p["wq"] >= 4 and p["nrt"] in (1, 2) and p["rg_max"] >= 1, (tag, p)
+    assert p["wq"] >= 4 and p["nrt"] in (1, 2, 4, 8) and p["rg_max"] >= 1, (tag, p)
     rows = R * T * (dims.n_q_heads // dims.n_kv_heads)
     assert p["rg_max"] * p["nrt"] * 32 >= rows, (tag, p)
     for c in range(p["chunks"]):
@@ -297,7 +297,7 @@ def test_attention_plan_bounds_over_the_admissible_shapes(monkeypatch):
                  (40, 200), (64, 512)]:
         for P in (0, 1, 31, 32, 100, 3072, 8192, 70000):
             shapes.append((F, S, P))
-    for variant in (None, "0", "1"):
+    for variant in (None, "0", "1", "2"):
         if variant is None:
             monkeypatch.delenv("FDC_ATTN_VARIANT", raising=False)
         else:
@@ -312,7 +312,7 @@ def test_attention_plan_bounds_over_the_admissible_shapes(monkeypatch):
                         continue
                     p = _check_plan(dims, tpl, B, R, T, (variant, F, S, P, Hq, Hkv, D, B, R, T))
                     seen.add((p["variant"], p["chunks"] > 1, p["tiles"] - p["prefix_tiles"] > p["max_masked_tiles"]))
-    assert len(seen) >= 6          # both kernels, one and several chunks, few and many slot tiles
+    assert len(seen) >= 8          # all three kernels, one and several chunks, few and many slot tiles
     # the five workloads as benchmarked
     from synth_inputs import model_dims
     for cfg, B, R, T in [(0, 1, 3, 1), (1, 1, 6, 1), (2, 1, 8, 1), (3, 16, 16, 1), (4, 8, 8, 4), (4, 8, 32, 4)]:
