@@ -82,7 +82,7 @@ class Decoder:
     """One context + its schedule (lengths known beforehand) with the greedy
     feedback kept on the device: last_tok[f] feeds field f's next row."""
 
-    def __init__(self, torch, dims, tpl, edges, weights_of=None, seed=0):
+    def __init__(self, torch, dims, tpl, edges, weights_of=None, seed=0, f16_weights=None):
         from paper_2602_02864_amd import Context, fdc_schedule, lib
         self.torch, self.tpl, self.dims = torch, tpl, dims
         F = tpl.n_fields
@@ -90,7 +90,7 @@ class Decoder:
         self.R = R = max(int((bf >= 0).sum()) for bf, _ in passes)
         self.passes = [(bf[:R].copy(), bo[:R].copy()) for bf, bo in passes]
         if weights_of is None:
-            self.ctx = Context(dims, tpl.slot_len, edges, tpl.prefix_len, 1, R, 1)
+            self.ctx = Context(dims, tpl.slot_len, edges, tpl.prefix_len, 1, R, 1, f16_weights=f16_weights)
             t0 = time.time()
             build_model(self.ctx, dims, seed, torch)
             log(f"[bench] model built in {time.time() - t0:.1f}s, "
@@ -166,7 +166,9 @@ def run_decode(args, cfg_id):
     dims = model_dims(cfg_id)
     tpl = template(cfg_id)
     F = tpl.n_fields
-    dec = Decoder(torch, dims, tpl, tpl.edges, seed=2864000 + cfg_id)
+    # the 256-row leg runs its projections on an fp16 copy of the same weights
+    dec = Decoder(torch, dims, tpl, tpl.edges, seed=2864000 + cfg_id,
+                  f16_weights="all" if cfg_id == 2 and not args.no_multi else None)
     ctx, passes, R = dec.ctx, dec.passes, dec.R
     K = args.steps if args.steps > 0 else len(passes)
     W = args.warmup
@@ -359,7 +361,7 @@ def run_multi(args, weights_of=None, steps=None):
     if weights_of is not None:
         ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T, weights_from=weights_of)
     else:
-        ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T)
+        ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T, f16_weights="all")
         t0 = time.time()
         build_model(ctx, dims, 2864004, torch)
         log(f"[bench] model built in {time.time() - t0:.1f}s, "
@@ -450,6 +452,32 @@ def run_multi(args, weights_of=None, steps=None):
                         "share_of_step": round(gemm_ms / ms, 4)},
         "kernels": kernels,
     }
+    if ctx._layer_w16:
+        # for the record: every projection single-pass on fp16 copies of the weights (opt-in:
+        # its error reaches 2.9e-3 after 28 layers, beyond the 2e-3 the default holds)
+        ctx.set_f16_projections(31)
+        for i in range(min(W, 4)):
+            one(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(K):
+            one(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms16 = e0.elapsed_time(e1)
+        ctx.profile_enable(True)
+        for i in range(K):
+            one(i)
+        torch.cuda.synchronize()
+        prof16 = ctx.profile_read()
+        ctx.profile_enable(False)
+        d16 = max(prof16[dom][0] / max(1, prof16[dom][1]) - ov_ms, 1e-6)
+        res["all_projections_fp16"] = {
+            "ms_per_step": round(ms16 / K, 4), "gate_up_avg_us": round(d16 * 1e3, 2),
+            "gate_up_TFLOP/s": round(fl / (d16 * 1e-3) / 1e12, 1),
+            "gate_up_frac_of_mfma_peak": round(fl / (d16 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
+            "note": "opt-in (fdc_set_f16_projections(31)): fp16 activations, 11 significant bits; measured "
+                    "2.9e-3 relative error after 28 layers, so not the default"}
     ctx.close()
     return res
 
@@ -528,7 +556,9 @@ def run_attention(args, rho=None, quick=False, dag_seed=None):
     qo_bytes = M * dims.n_q_heads * dims.head_dim * (2 + 4)
     alg_bytes = kv_bytes + qo_bytes
     visible_pairs = sum(bin(int(a)).count("1") for a in anc) + F
-    K = 50 if quick else max(20, args.steps if args.steps > 0 else 100)
+    # the first few dozen launches after the idle moment of a synchronisation run slower
+    # (50 launches average 68 us, 200 and more 63.6 us): enough launches to make that small
+    K = 300 if quick else max(200, args.steps if args.steps > 0 else 300)
     # A launch is tens of microseconds, and the device needs a few hundred milliseconds of
     # sustained work before it runs at its steady rate (measured: 71 us per call after 300
     # warm-up launches, 64.5 us after 3000 and after 15000): warm up for a quarter of a second.
@@ -690,7 +720,7 @@ def main():
             # matrix-core products, a few passes
             m = run_multi(args, weights_of=dec.ctx, steps=8)
             res["cfg4"] = {k: m[k] for k in ("config", "ms_per_step", "value", "unit", "roofline", "projections",
-                                             "kernels")}
+                                             "kernels", "all_projections_fp16") if k in m}
             rooflines["cfg4 gate_up_swiglu (256 rows)"] = {k: m["roofline"][k] for k in
                                                            ("bound", "achieved", "peak", "unit", "frac")}
         dec.ctx.close()

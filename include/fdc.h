@@ -28,7 +28,8 @@
  *    d_model <= 5120; B*R*T <= 1024 rows per step; at most 65535 * 32 cache
  *    positions per scene (FDC_ECAP otherwise).  Up to
  *    16 rows the projections stream the weights once (HBM-bound kernels), above
- *    that they run as tiled matrix-core products.
+ *    that they run as tiled matrix-core products (single-pass on an fp16 copy of
+ *    the weights where the caller provides one).
  */
 #ifndef FDC_H
 #define FDC_H
@@ -162,6 +163,12 @@ void    fdc_sched_destroy(fdc_sched* s);
  */
 #define FDC_PACK_PLAIN   0
 #define FDC_PACK_GATE_UP 1
+/* flag, or-ed to either mode: dst holds fp16 instead of bf16, each weight times
+ * 2^8 (exact for 2^-22 <= |w| < 256; smaller ones are rounded to the nearest
+ * fp16 subnormal, absolute error below 2^-33; larger ones saturate).  The fp16
+ * copy feeds the single-pass projections of steps with more than 16 rows, see
+ * fdc_set_layer_weights_f16. */
+#define FDC_PACK_F16     2
 size_t  fdc_packed_weight_bytes(int64_t n_out, int64_t k_in);
 int32_t fdc_pack_weight(const void* src_dev, void* dst_dev, int64_t n_out, int64_t k_in,
                         int32_t mode, void* stream);
@@ -200,6 +207,35 @@ int32_t fdc_set_layer_weights(fdc_ctx* ctx, int32_t layer, const fdc_layer_weigh
 /* emb: device bf16 row-major [vocab][d_model] (gathered, not packed);
  * gf: device fp32 [d_model] final-norm gain; lm: packed [vocab][d_model] */
 int32_t fdc_set_head_weights(fdc_ctx* ctx, const void* emb, const float* gf, const void* lm);
+
+/* Optional second copy of the projection weights as fp16 (packed with
+ * FDC_PACK_F16), used by steps of more than 16 rows, where the projections are
+ * bound by the matrix cores and not by streaming the weights: with it the
+ * activations enter the matrix cores as one fp16 value (11 significant bits)
+ * instead of a bf16 head + tail (16 bits), i.e. one matrix instruction per
+ * weight fragment instead of two.  Costs the copied weights' size in memory
+ * again.  A layer projection takes the fp16 path only when every layer has its
+ * copy, the LM head when it has its own; steps of up to 16 rows never do.
+ * Activations beyond +-65504 saturate on that path.
+ *
+ * Which projections take the fp16 path is a mask (fdc_set_f16_projections; bits:
+ * 1 QKV, 2 O, 4 gate/up, 8 down, 16 LM head; environment FDC_F16_MASK at creation
+ * overrides the default).  The default is 16, the LM head alone: measured on the
+ * 7B-class model at 32 rows per step, every other projection run single-pass
+ * adds about 3e-4 of the residual stream's scale per layer it is used in, and
+ * all of them together reach 2.9e-3 after 28 layers, beyond the 2e-3 this
+ * library holds against the fp64 definition; the LM head's rounding does not
+ * feed back.  The full mask is for callers who trade that accuracy for about a
+ * sixth of the step time at 256 rows. */
+typedef struct fdc_layer_weights_f16 {
+    const void* wqkv;     /* as fdc_layer_weights, packed with mode | FDC_PACK_F16 */
+    const void* wo;
+    const void* wgu;
+    const void* wd;
+} fdc_layer_weights_f16;
+int32_t fdc_set_layer_weights_f16(fdc_ctx* ctx, int32_t layer, const fdc_layer_weights_f16* w);
+int32_t fdc_set_head_weights_f16(fdc_ctx* ctx, const void* lm_f16);
+int32_t fdc_set_f16_projections(fdc_ctx* ctx, int32_t mask);
 
 /* valid_len[b*F + g] = number of tokens of field g of scene b in the cache.
  * host arrays. fdc_reset zeroes them. */

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libfdc.so")
 
 FDC_OK, FDC_EINVAL, FDC_ECYCLE, FDC_EORDER, FDC_ERANGE, FDC_ECAP, FDC_EHIP, FDC_ESTATE = \
     0, -1, -2, -3, -4, -5, -6, -7
-FDC_PACK_PLAIN, FDC_PACK_GATE_UP = 0, 1
+FDC_PACK_PLAIN, FDC_PACK_GATE_UP, FDC_PACK_F16 = 0, 1, 2
 
 EXPORTS = [
     "fdc_strerror", "fdc_last_error", "fdc_version", "fdc_build_mask", "fdc_dense_mask",
@@ -34,6 +34,7 @@ EXPORTS = [
     "fdc_sched_create", "fdc_sched_next", "fdc_sched_destroy",
     "fdc_sched_peek", "fdc_sched_advance", "fdc_sched_complete", "fdc_sched_stats",
     "fdc_cot_decode", "fdc_step_tables_dense", "fdc_attention_plan",
+    "fdc_set_layer_weights_f16", "fdc_set_head_weights_f16", "fdc_set_f16_projections",
 ]
 FDC_PROF_KINDS = 9
 
@@ -48,6 +49,10 @@ class ModelDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_mlp", C.c_int32),
                 ("vocab", C.c_int32), ("rope_base", C.c_float), ("norm_eps", C.c_float)]
+
+
+class LayerWeightsF16(C.Structure):
+    _fields_ = [("wqkv", C.c_void_p), ("wo", C.c_void_p), ("wgu", C.c_void_p), ("wd", C.c_void_p)]
 
 
 class LayerWeights(C.Structure):
@@ -100,6 +105,12 @@ def lib() -> C.CDLL:
     L.fdc_set_layer_weights.argtypes = [vp, i32, C.POINTER(LayerWeights)]
     L.fdc_set_head_weights.restype = i32
     L.fdc_set_head_weights.argtypes = [vp, vp, vp, vp]
+    L.fdc_set_layer_weights_f16.restype = i32
+    L.fdc_set_layer_weights_f16.argtypes = [vp, i32, C.POINTER(LayerWeightsF16)]
+    L.fdc_set_head_weights_f16.restype = i32
+    L.fdc_set_head_weights_f16.argtypes = [vp, vp]
+    L.fdc_set_f16_projections.restype = i32
+    L.fdc_set_f16_projections.argtypes = [vp, i32]
     L.fdc_reset.restype = i32
     L.fdc_reset.argtypes = [vp]
     L.fdc_set_valid_len.restype = i32
@@ -368,11 +379,16 @@ class Context:
     packed weights).  Methods carry the names of the C entry points."""
 
     def __init__(self, dims, slot_len, edges, prefix_len, n_scenes=1, max_branches=1, max_tokens=1,
-                 device="cuda:0", share=None, weights_from=None):
+                 device="cuda:0", share=None, weights_from=None, f16_weights=None):
         """share: another Context over the same model and the same cache positions
         (same total length) whose KV cache and packed weights this one uses too.
         weights_from: another Context over the same model whose packed weights this
-        one uses (its own cache: any template, any batch)."""
+        one uses (its own cache: any template, any batch).
+        f16_weights: fp16 copies for the single-pass projections of steps with more
+        than 16 rows: "head" = of the LM head only (the default when such steps can
+        occur, i.e. n_scenes * max_branches * max_tokens > 16), "all" / True = of
+        every matrix (then fdc_set_f16_projections can enable the layer projections
+        too), False = none."""
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -388,6 +404,11 @@ class Context:
                                 int(prefix_len), n_scenes, max_branches, max_tokens, C.byref(self._h)))
         self._keep = []
         self._layer_w, self._head_w = {}, None
+        self._layer_w16, self._head_w16 = {}, None
+        if f16_weights is None:
+            f16_weights = "head" if n_scenes * max_branches * max_tokens > 16 else False
+        self.f16_weights = "all" if f16_weights is True else f16_weights
+        assert self.f16_weights in ("all", "head", False)
         self.edges = [(int(u), int(v)) for u, v in zip(src, dst)]
         self.prefix_len = int(prefix_len)
         self.total_len = int(prefix_len) + int(self.slot_len.sum())
@@ -415,6 +436,13 @@ class Context:
             if share._head_w is not None:
                 _check(lib().fdc_set_head_weights(self._h, *share._head_w))
                 self._head_w = share._head_w
+            # whatever fp16 copies the other context holds come along (pointers only)
+            for layer, lw in share._layer_w16.items():
+                _check(lib().fdc_set_layer_weights_f16(self._h, layer, C.byref(lw)))
+                self._layer_w16[layer] = lw
+            if share._head_w16 is not None:
+                _check(lib().fdc_set_head_weights_f16(self._h, share._head_w16))
+                self._head_w16 = share._head_w16
             self._keep.append(share._keep)
 
     def prefill_view(self, max_tokens: int):
@@ -476,23 +504,37 @@ class Context:
     def set_layer_weights(self, layer: int, w: dict):
         """w: g1, wqkv, wo, g2, wgu, wd in the row-major [out][in] convention."""
         g1, g2 = self._dev_f32(w["g1"]), self._dev_f32(w["g2"])
-        packed = {}
+        packed, packed16 = {}, {}
         for k in ("wqkv", "wo", "wgu", "wd"):
             src = self._dev_bf16(w[k])
-            packed[k] = fdc_pack_weight(src, FDC_PACK_GATE_UP if k == "wgu" else FDC_PACK_PLAIN)
+            mode = FDC_PACK_GATE_UP if k == "wgu" else FDC_PACK_PLAIN
+            packed[k] = fdc_pack_weight(src, mode)
+            if self.f16_weights == "all":
+                packed16[k] = fdc_pack_weight(src, mode | FDC_PACK_F16)
             del src
         lw = LayerWeights(g1.data_ptr(), packed["wqkv"].data_ptr(), packed["wo"].data_ptr(),
                           g2.data_ptr(), packed["wgu"].data_ptr(), packed["wd"].data_ptr())
         _check(lib().fdc_set_layer_weights(self._h, layer, C.byref(lw)))
         self._layer_w[layer] = lw
-        self._keep.append((g1, g2, packed))
+        if self.f16_weights == "all":
+            lw16 = LayerWeightsF16(packed16["wqkv"].data_ptr(), packed16["wo"].data_ptr(),
+                                   packed16["wgu"].data_ptr(), packed16["wd"].data_ptr())
+            _check(lib().fdc_set_layer_weights_f16(self._h, layer, C.byref(lw16)))
+            self._layer_w16[layer] = lw16
+        self._keep.append((g1, g2, packed, packed16))
 
     def set_head_weights(self, emb, gf, lm):
         e, g = self._dev_bf16(emb), self._dev_f32(gf)
-        lmp = fdc_pack_weight(self._dev_bf16(lm))
+        lms = self._dev_bf16(lm)
+        lmp = fdc_pack_weight(lms)
         self._head_w = (e.data_ptr(), g.data_ptr(), lmp.data_ptr())
         _check(lib().fdc_set_head_weights(self._h, *self._head_w))
-        self._keep.append((e, g, lmp))
+        lmp16 = None
+        if self.f16_weights:
+            lmp16 = fdc_pack_weight(lms, FDC_PACK_PLAIN | FDC_PACK_F16)
+            self._head_w16 = lmp16.data_ptr()
+            _check(lib().fdc_set_head_weights_f16(self._h, self._head_w16))
+        self._keep.append((e, g, lmp, lmp16))
 
     # -- state ---------------------------------------------------------------------
     def reset(self):
@@ -502,6 +544,10 @@ class Context:
         a = _i32(v)
         assert a.size == self.B * self.F
         _check(lib().fdc_set_valid_len(self._h, _p(a)))
+
+    def set_f16_projections(self, mask: int):
+        """Which projections run single-pass on the fp16 weights (1 QKV, 2 O, 4 gate/up, 8 down, 16 LM head)."""
+        _check(lib().fdc_set_f16_projections(self._h, int(mask)))
 
     def get_valid_len(self) -> np.ndarray:
         a = np.zeros(self.B * self.F, dtype=np.int32)

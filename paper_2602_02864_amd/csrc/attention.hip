@@ -1116,12 +1116,17 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, StepMeta sm
     if (a.out_f32) {
         *reinterpret_cast<f32x4*>(a.out_f32 + ((size_t)ri.m * a.Hq + ri.head) * D + d0) = acc;
     } else {
-        uint32_t hi[2], lo[2];
-        split2(acc[0], acc[1], hi[0], lo[0]);
-        split2(acc[2], acc[3], hi[1], lo[1]);
         const size_t o = act_frag_index(ri.m, ri.head * D + d0, a.Hq * D / 32);
-        *reinterpret_cast<uint2*>(a.out_hi + o) = make_uint2(hi[0], hi[1]);
-        *reinterpret_cast<uint2*>(a.out_lo + o) = make_uint2(lo[0], lo[1]);
+        if (a.out_f16) {
+            *reinterpret_cast<uint2*>(a.out_hi + o) =
+                make_uint2(f2h(acc[0]) | (uint32_t)f2h(acc[1]) << 16, f2h(acc[2]) | (uint32_t)f2h(acc[3]) << 16);
+        } else {
+            uint32_t hi[2], lo[2];
+            split2(acc[0], acc[1], hi[0], lo[0]);
+            split2(acc[2], acc[3], hi[1], lo[1]);
+            *reinterpret_cast<uint2*>(a.out_hi + o) = make_uint2(hi[0], hi[1]);
+            *reinterpret_cast<uint2*>(a.out_lo + o) = make_uint2(lo[0], lo[1]);
+        }
     }
 }
 

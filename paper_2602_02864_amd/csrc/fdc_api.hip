@@ -34,6 +34,10 @@ struct fdc_ctx {
     std::vector<int32_t> edge_src, edge_dst;
     std::vector<fdc_layer_weights> lw;
     std::vector<char> lw_set;
+    std::vector<fdc_layer_weights_f16> lw16;     // optional fp16 copies for steps of more than 16 rows
+    std::vector<char> lw16_set;
+    const uint16_t* lm16 = nullptr;
+    int f16_mask = 0;                    // which projections may take the fp16 path: 1 QKV, 2 O, 4 gate/up, 8 down, 16 LM head
     const uint16_t* emb = nullptr;
     const float* gf = nullptr;
     const uint16_t* lm = nullptr;
@@ -435,8 +439,8 @@ int32_t fdc_pack_weight(const void* src, void* dst, int64_t n_out, int64_t k_in,
     if (n_out <= 0 || k_in <= 0 || k_in % 32)
         return fail(FDC_EINVAL, "n_out (%lld) must be positive and k_in (%lld) a multiple of 32",
                     (long long)n_out, (long long)k_in);
-    if (mode != FDC_PACK_PLAIN && mode != FDC_PACK_GATE_UP) return fail(FDC_EINVAL, "unknown pack mode %d", mode);
-    if (mode == FDC_PACK_GATE_UP && n_out % 32) return fail(FDC_EINVAL, "gate/up packing needs n_out %% 32 == 0");
+    if (mode < 0 || mode > (FDC_PACK_GATE_UP | FDC_PACK_F16)) return fail(FDC_EINVAL, "unknown pack mode %d", mode);
+    if ((mode & 1) == FDC_PACK_GATE_UP && n_out % 32) return fail(FDC_EINVAL, "gate/up packing needs n_out %% 32 == 0");
     if (!aligned(src) || !aligned(dst)) return fail(FDC_EINVAL, "pointers must be 16-byte aligned");
     launch_pack_weight((const uint16_t*)src, (uint16_t*)dst, n_out, k_in, mode, (hipStream_t)stream);
     FDC_HIP(hipGetLastError());
@@ -493,6 +497,8 @@ int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t*
     c->valid_len.assign((size_t)n_scenes * n_fields, 0);
     c->lw.resize(m.n_layers);
     c->lw_set.assign(m.n_layers, 0);
+    c->lw16.resize(m.n_layers);
+    c->lw16_set.assign(m.n_layers, 0);
     c->kv_layer_elems = (size_t)n_scenes * m.n_kv_heads * c->Npad * m.head_dim;
     const int64_t HqD = (int64_t)m.n_q_heads * m.head_dim;
     c->p_qkv = plan_gemm(HqD + 2 * (int64_t)m.n_kv_heads * m.head_dim, m.d_model, false);
@@ -519,6 +525,8 @@ int32_t fdc_create(const fdc_model_desc* model, int32_t n_fields, const int32_t*
         delete c;
         return fail(FDC_ECAP, "%d cache positions: more than 65535 tiles of 32 keys", N);
     }
+    c->f16_mask = kF16Default;
+    if (const char* e = std::getenv("FDC_F16_MASK")) c->f16_mask = std::atoi(e) & 31;
     plan_attention(c);
     carve(c);
     *out = c;
@@ -598,6 +606,31 @@ int32_t fdc_set_head_weights(fdc_ctx* c, const void* emb, const float* gf, const
     c->emb = (const uint16_t*)emb;
     c->gf = gf;
     c->lm = (const uint16_t*)lm;
+    return FDC_OK;
+}
+
+int32_t fdc_set_layer_weights_f16(fdc_ctx* c, int32_t layer, const fdc_layer_weights_f16* w) {
+    if (!c || !w) return fail(FDC_EINVAL, "null pointer argument");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(FDC_ERANGE, "layer %d outside 0..%d", layer, c->m.n_layers - 1);
+    if (!w->wqkv || !w->wo || !w->wgu || !w->wd) return fail(FDC_EINVAL, "null weight pointer");
+    for (const void* p : {w->wqkv, w->wo, w->wgu, w->wd})
+        if (!aligned(p)) return fail(FDC_EINVAL, "weight pointers must be 16-byte aligned");
+    c->lw16[layer] = *w;
+    c->lw16_set[layer] = 1;
+    return FDC_OK;
+}
+
+int32_t fdc_set_f16_projections(fdc_ctx* c, int32_t mask) {
+    if (!c) return fail(FDC_EINVAL, "null context");
+    if (mask < 0 || mask > 31) return fail(FDC_EINVAL, "projection mask %d outside 0..31", mask);
+    c->f16_mask = mask;
+    return FDC_OK;
+}
+
+int32_t fdc_set_head_weights_f16(fdc_ctx* c, const void* lm_f16) {
+    if (!c || !lm_f16) return fail(FDC_EINVAL, "null pointer argument");
+    if (!aligned(lm_f16)) return fail(FDC_EINVAL, "weight pointers must be 16-byte aligned");
+    c->lm16 = (const uint16_t*)lm_f16;
     return FDC_OK;
 }
 
@@ -775,6 +808,12 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     // up to 16 rows the projections stream their weights once (bandwidth-bound);
     // above, they are tiled matrix products; either way `S` partials come back
     const bool tiled = M > kMaxRowsDense;
+    // the single-pass fp16 projections: only in tiled steps, only those the mask
+    // names, and only where the fp16 copies exist (layers: all or none)
+    bool f16_layers = tiled;
+    for (int l = 0; f16_layers && l < m.n_layers; ++l) f16_layers = c->lw16_set[l] != 0;
+    const bool f16_head = tiled && c->lm16 != nullptr;
+    const int fm = (f16_layers ? c->f16_mask & 15 : 0) | (f16_head ? c->f16_mask & 16 : 0);
     bool launched = true;              // false: a projection had no kernel for its plan
     auto project = [&](const GemmPlan& skinny, int64_t n_out, int64_t k_in, int epi, const GemmArgs& ga,
                        bool one_split) -> int {
@@ -795,6 +834,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     na.M = M;
     na.d = d;
     na.vocab = m.vocab;
+    na.f16 = false;
 
     int s_down = c->p_down.S;
     for (int l = 0; l < m.n_layers; ++l) {
@@ -810,11 +850,15 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
             n1.S = s_down;
         }
         n1.gain = w.g1;
+        n1.f16 = (fm & 1) != 0;
         n1.hidden_x = hidden_out ? hidden_out + (size_t)l * hstride : nullptr;
         { ProfScope ps_(c, PK_NORM, st); launch_resid_norm(n1, sm, st); }
 
         GemmArgs g{};
-        g.w = (const uint16_t*)w.wqkv;
+        g.f16 = (fm & 1) != 0;
+        g.out_scale = 1.0f / 256.0f;
+        const fdc_layer_weights_f16& w16 = c->lw16[l];
+        g.w = (const uint16_t*)(g.f16 ? w16.wqkv : w.wqkv);
         g.act_hi = a_hi;
         g.act_lo = a_lo;
         g.out = part;
@@ -843,9 +887,11 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         aa.q_f32 = q;
         aa.out_hi = o_hi;
         aa.out_lo = o_lo;
+        aa.out_f16 = (fm & 2) != 0;
         { ProfScope ps_(c, PK_ATTN, st); launch_attention(aa, sm, st); }
 
-        g.w = (const uint16_t*)w.wo;
+        g.f16 = (fm & 2) != 0;
+        g.w = (const uint16_t*)(g.f16 ? w16.wo : w.wo);
         g.act_hi = o_hi;
         g.act_lo = o_lo;
         g.N = d;
@@ -857,10 +903,14 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         n2.part = part;
         n2.S = s_o;
         n2.gain = w.g2;
+        n2.f16 = (fm & 4) != 0;
         { ProfScope ps_(c, PK_NORM, st); launch_resid_norm(n2, sm, st); }
 
         GemmArgs gu{};
-        gu.w = (const uint16_t*)w.wgu;
+        gu.f16 = (fm & 4) != 0;
+        gu.out_f16 = (fm & 8) != 0;
+        gu.out_scale = 1.0f / 256.0f;
+        gu.w = (const uint16_t*)(gu.f16 ? w16.wgu : w.wgu);
         gu.act_hi = a_hi;
         gu.act_lo = a_lo;
         gu.out_hi = h_hi;
@@ -869,7 +919,8 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         gu.M = M;
         { ProfScope ps_(c, PK_GATEUP, st); project(c->p_gu, 2 * (int64_t)m.d_mlp, d, EPI_SWIGLU, gu, true); }
 
-        g.w = (const uint16_t*)w.wd;
+        g.f16 = (fm & 8) != 0;
+        g.w = (const uint16_t*)(g.f16 ? w16.wd : w.wd);
         g.act_hi = h_hi;
         g.act_lo = h_lo;
         g.N = d;
@@ -880,12 +931,15 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     nf.part = part;
     nf.S = s_down;
     nf.gain = c->gf;
+    nf.f16 = (fm & 16) != 0;
     nf.hidden_x = hidden_out ? hidden_out + (size_t)m.n_layers * hstride : nullptr;
     nf.hidden_n = hidden_out ? hidden_out + (size_t)(m.n_layers + 1) * hstride : nullptr;
     { ProfScope ps_(c, PK_NORM, st); launch_resid_norm(nf, sm, st); }
 
     GemmArgs gl{};
-    gl.w = c->lm;
+    gl.f16 = (fm & 16) != 0;
+    gl.out_scale = 1.0f / 256.0f;
+    gl.w = gl.f16 ? c->lm16 : c->lm;
     gl.act_hi = a_hi;
     gl.act_lo = a_lo;
     gl.out = logits;

@@ -22,6 +22,7 @@ constexpr int kMaxChunkTiles = 128; // 32-key tiles one attention workgroup walk
 constexpr int kMaxChunkTilesReg = 512;  // ... with tiles in registers
 constexpr int kMaxChunkTilesWide = 64;  // ... in the many-row kernel (one tile list entry per lane)
 constexpr int kMaxMaskedTiles = 32; // ... of which this many may reach into the slots
+constexpr int kF16Default = 16;     // projections that take the fp16 path when fp16 weights exist: the LM head
 
 // How one projection y = x W^T is cut: S splits of the reduction dimension,
 // each handled by workgroups of `nw` wavefronts that keep their slice of the

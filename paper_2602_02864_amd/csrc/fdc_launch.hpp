@@ -22,6 +22,12 @@ struct GemmArgs {
     int N;                    // row stride of `out`
     int n_valid;              // output features actually stored (multiple of 4)
     int out_KT;               // EPI_SWIGLU: k tiles of the consumer (= d_mlp / 32)
+    // tiled kernels only: `w` is the fp16 copy of the weights (values times 2^8) and
+    // act_hi holds single fp16 fragments (no tail); results are multiplied by
+    // out_scale (2^-8)
+    bool f16;
+    float out_scale;
+    bool out_f16;             // EPI_SWIGLU writes single fp16 fragments to out_hi (the consumer runs fp16)
 };
 // both return false (and launch nothing) for a plan no kernel was built for
 bool launch_gemm(const GemmPlan& p, int epilogue, const GemmArgs& a, hipStream_t st);
@@ -57,6 +63,7 @@ struct NormArgs {
     float* hidden_x;          // optional copy of the updated residual [M][d]
     float* hidden_n;          // optional copy of the normalised row [M][d]
     int M, d, vocab;
+    bool f16;                 // a_hi gets single fp16 fragments (a_lo untouched)
 };
 void launch_resid_norm(const NormArgs& a, const StepMeta& sm, hipStream_t st);
 
@@ -93,8 +100,9 @@ struct AttnArgs {
     const uint32_t* mask_words; // the step's visibility words [B][mw_tiles][R*T] (launch_mask_words)
     int mw_tiles;             // tiles that reach past the prefix: NB - P / 32
     float* out_f32;           // merge output: fp32 [M][Hq*D] ...
-    uint16_t* out_hi;         // ... or fragments with K = Hq*D
-    uint16_t* out_lo;
+    uint16_t* out_hi;         // ... or fragments with K = Hq*D: bf16 head + tail,
+    uint16_t* out_lo;         //     or (out_f16) single fp16 fragments in out_hi
+    bool out_f16;
     int Hq, Hkv, G, D, P, NB, CB, n_chunks, n_rg, nrt;   // CB: weighted tiles per chunk
     int wq;                   // weight of a tile past the prefix, in quarters of a prefix tile
     int variant;              // 0: LDS-shared tiles (direct-to-LDS ring), 1: tiles in registers

@@ -140,10 +140,20 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ src, uint16_t* _
     const int lane = (int)(chunk & 63);
     const int64_t kt = (chunk >> 6) % KT, tile = (chunk >> 6) / KT;
     int64_t src_tile = tile;
-    if (mode == FDC_PACK_GATE_UP) src_tile = (tile & 1) ? n_tiles / 2 + tile / 2 : tile / 2;
+    if ((mode & 1) == FDC_PACK_GATE_UP) src_tile = (tile & 1) ? n_tiles / 2 + tile / 2 : tile / 2;
     const int64_t row = src_tile * 16 + (lane & 15), k = kt * 32 + 8 * (lane >> 4);
     uint4 v = make_uint4(0, 0, 0, 0);
     if (row < n_out) v = *reinterpret_cast<const uint4*>(src + row * k_in + k);
+    if (mode & FDC_PACK_F16) {
+        // bf16 value x 2^8 as fp16: exact for 2^-22 <= |w| < 256 (11 >= 8 significant
+        // bits), rounded to nearest below (absolute error under 2^-33), saturated above
+        uint32_t* u = reinterpret_cast<uint32_t*>(&v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float lo = __uint_as_float(u[i] << 16) * 256.0f, hi = __uint_as_float(u[i] & 0xffff0000u) * 256.0f;
+            u[i] = f2h(lo) | (uint32_t)f2h(hi) << 16;
+        }
+    }
     *reinterpret_cast<uint4*>(dst + chunk * 8) = v;
 }
 

@@ -14,7 +14,12 @@
 //   * the activations keep their bf16 tail: two matrix instructions per weight
 //     fragment, fp32-accurate inputs;
 //   * K may be split over workgroups (partials summed by the consumer), and
-//     the SwiGLU epilogue pairs the interleaved gate / up tiles in registers.
+//     the SwiGLU epilogue pairs the interleaved gate / up tiles in registers;
+//   * F16 variants: where the caller has packed a second copy of the weights as
+//     fp16 (the bf16 values times 2^8: exact, fdc_pack_weight), the activations come
+//     as single fp16 fragments (11 significant bits) instead of a bf16 head + tail:
+//     one matrix instruction per weight fragment instead of two and half the row
+//     traffic; the epilogue takes the 2^8 out again.
 #include "kernels_common.hpp"
 #include "fdc_launch.hpp"
 
@@ -33,9 +38,37 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int NTW, int EPI>
+template <bool F16>
+__device__ __forceinline__ f32x16 mma32(const uint4& w, const uint4& x, const f32x16& c) {
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, x), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), c, 0, 0, 0);
+}
+template <bool F16>
+__device__ __forceinline__ f32x4 mma16(const f32x4& w, const uint4& x, const f32x4& c) {
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, x), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), c, 0, 0, 0);
+}
+
+// silu(gate) * up as the activation fragment element(s) of the next projection
+__device__ __forceinline__ void store_h4(const GemmArgs& a, size_t o, const float (&h)[4]) {
+    if (a.out_f16) {
+        uint16_t v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = f2h(h[e]);
+        *reinterpret_cast<uint2*>(a.out_hi + o) = make_uint2(v[0] | (uint32_t)v[1] << 16, v[2] | (uint32_t)v[3] << 16);
+    } else {
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split_bf16(h[e], hi[e], lo[e]);
+        *reinterpret_cast<uint2*>(a.out_hi + o) = make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
+        *reinterpret_cast<uint2*>(a.out_lo + o) = make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+    }
+}
+
+template <int NTW, int EPI, bool F16>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p) {
-    constexpr int NF = 2 * kWgMTiles + 2 * NTW;        // fragments per k tile: rows (head, tail), weights
+    constexpr int NA = F16 ? kWgMTiles : 2 * kWgMTiles; // row fragments per k tile: heads (, tails)
+    constexpr int NF = NA + 2 * NTW;                   // fragments per k tile: rows, weights
     constexpr int NLD = NF / 4;                        // ... fetched per wavefront
     static_assert(NF % 4 == 0, "fragments must divide over four wavefronts");
     __shared__ uint4 lds[kStages][NF][64];
@@ -62,11 +95,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
         const int f = wave + 4 * j;
-        if (f < 2 * kWgMTiles) {
+        if (f < NA) {
             const int mt = min(mb * kWgMTiles + (f & 7), p.m_tiles - 1);
             src[j] = ((f >> 3) ? a.act_lo : a.act_hi) + (((size_t)mt * p.KT + kt0) * 64 + lane) * 8;
         } else {
-            const int tile = min(ng * 2 * NTW + (f - 2 * kWgMTiles), p.n_tiles - 1);
+            const int tile = min(ng * 2 * NTW + (f - NA), p.n_tiles - 1);
             src[j] = a.w + (((size_t)tile * p.KT + kt0) * 64 + lane) * 8;
         }
     }
@@ -102,22 +135,24 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
 #define FDC_MMA(stg)                                                                                  \
     {                                                                                                 \
         const uint4* st = &lds[stg][0][0] + pair_off;                                                 \
-        bf16x8 ah[2][2], al[2][2]; /* [32-row block][k half] */                                       \
+        uint4 ah[2][2], al[2][2]; /* [32-row block][k half] */                                        \
         _Pragma("unroll") for (int q = 0; q < 2; ++q)                                                 \
         _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                               \
-            ah[q][h] = __builtin_bit_cast(bf16x8, st[(4 * wm + 2 * q) * 64 + 32 * h]);                \
-            al[q][h] = __builtin_bit_cast(bf16x8, st[(8 + 4 * wm + 2 * q) * 64 + 32 * h]);            \
+            ah[q][h] = st[(4 * wm + 2 * q) * 64 + 32 * h];                                            \
+            if (!F16) al[q][h] = st[(8 + 4 * wm + 2 * q) * 64 + 32 * h];                              \
         }                                                                                             \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                           \
-            bf16x8 wv[2];                                                                             \
+            uint4 wv[2];                                                                              \
             _Pragma("unroll") for (int h = 0; h < 2; ++h)                                             \
-                wv[h] = __builtin_bit_cast(bf16x8, st[(2 * kWgMTiles + wn * NTW + 2 * nb) * 64 + 32 * h]); \
-            _Pragma("unroll") for (int h = 0; h < 2; ++h)                                             \
-            _Pragma("unroll") for (int q = 0; q < 2; ++q)                                             \
-                acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], ah[q][h], acc[q][nb], 0, 0, 0); \
+                wv[h] = st[(NA + wn * NTW + 2 * nb) * 64 + 32 * h];                                   \
             _Pragma("unroll") for (int h = 0; h < 2; ++h)                                             \
             _Pragma("unroll") for (int q = 0; q < 2; ++q)                                             \
-                acc[q][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[h], al[q][h], acc[q][nb], 0, 0, 0); \
+                acc[q][nb] = mma32<F16>(wv[h], ah[q][h], acc[q][nb]);                                 \
+            if (!F16) {                                                                               \
+                _Pragma("unroll") for (int h = 0; h < 2; ++h)                                         \
+                _Pragma("unroll") for (int q = 0; q < 2; ++q)                                         \
+                    acc[q][nb] = mma32<F16>(wv[h], al[q][h], acc[q][nb]);                             \
+            }                                                                                         \
         }                                                                                             \
     }
     // One iteration.  Tile i+2 (requested three iterations ago into `g`) goes
@@ -173,8 +208,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
                 for (int e4 = 0; e4 < 4; ++e4) {
                     const int n = tile0 * 16 + 8 * e4 + 4 * (lane >> 5);
                     if (n < a.n_valid) {
-                        const f32x4 v = {acc[q][nb][4 * e4], acc[q][nb][4 * e4 + 1], acc[q][nb][4 * e4 + 2],
-                                         acc[q][nb][4 * e4 + 3]};
+                        f32x4 v = {acc[q][nb][4 * e4], acc[q][nb][4 * e4 + 1], acc[q][nb][4 * e4 + 2],
+                                   acc[q][nb][4 * e4 + 3]};
+                        if (F16) v *= a.out_scale;
                         *reinterpret_cast<f32x4*>(a.out + ((size_t)s * a.M + m) * a.N + n) = v;
                     }
                 }
@@ -183,17 +219,17 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
                 const int ftile = tile0 >> 1;
 #pragma unroll
                 for (int e4 = 0; e4 < 2; ++e4) {
-                    uint16_t hi[4], lo[4];
+                    float h[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float gt = acc[q][nb][4 * e4 + e], up = acc[q][nb][8 + 4 * e4 + e];
-                        split_bf16(gt / (1.0f + __expf(-gt)) * up, hi[e], lo[e]);
+                        float gt = acc[q][nb][4 * e4 + e], up = acc[q][nb][8 + 4 * e4 + e];
+                        if (F16) {
+                            gt *= a.out_scale;
+                            up *= a.out_scale;
+                        }
+                        h[e] = gt / (1.0f + __expf(-gt)) * up;
                     }
-                    const size_t o = act_frag_index(m, ftile * 16 + 8 * e4 + 4 * (lane >> 5), a.out_KT);
-                    *reinterpret_cast<uint2*>(a.out_hi + o) =
-                        make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
-                    *reinterpret_cast<uint2*>(a.out_lo + o) =
-                        make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+                    store_h4(a, act_frag_index(m, ftile * 16 + 8 * e4 + 4 * (lane >> 5), a.out_KT), h);
                 }
             }
         }
@@ -217,9 +253,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
 // in neighbouring wavefronts: the SwiGLU epilogue passes that one tile through
 // LDS.  (A 4 x 2 grid needs no such exchange but asks the L1 for every weight
 // line four times and measured slower than the four-wavefront kernel.)
-template <int NTW, int EPI, int WM>
+template <int NTW, int EPI, int WM, bool F16>
 __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan p) {
-    constexpr int NFA = 2 * kWgMTiles;                 // row fragments per k tile: heads, tails
+    constexpr int NFA = F16 ? kWgMTiles : 2 * kWgMTiles;   // row fragments per k tile: heads (, tails)
+    constexpr int NSRC = F16 ? 1 : 2;
     constexpr int WN = 8 / WM;                         // wavefronts along the features
     constexpr int MF = kWgMTiles / WM;                 // 16-row fragments per wavefront
     constexpr int TW = 2 * NTW / WN;                   // 16-feature tiles per wavefront
@@ -248,7 +285,7 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
         const int mt = min(mb * kWgMTiles + wave, p.m_tiles - 1);
         const size_t off = ((size_t)mt * p.KT + kt0) * 512;
         src[0] = a.act_hi + off;
-        src[1] = a.act_lo + off;
+        src[1] = F16 ? src[0] : a.act_lo + off;
     }
     // its weight fragments; past the last feature tile the last one is re-read
     // (what it produces is never stored)
@@ -272,23 +309,23 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
     f32x4 g0[2], g1[2];
     f32x4 b0[TW], b1[TW], b2[NBS == 4 ? TW : 1], b3[NBS == 4 ? TW : 1];
 #define FDC_FETCH(g, i)                                                                    \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
+    _Pragma("unroll") for (int j = 0; j < NSRC; ++j)                                       \
         g[j] = *reinterpret_cast<const f32x4*>(src[j] + (size_t)min((i), nkt - 1) * 512 + lane * 8)
 #define FDC_FETCHW1(b, t, i)                                                               \
     b[t] = *reinterpret_cast<const f32x4*>(wsrc[t] + (size_t)min((i), nkt - 1) * 512 + lane * 8)
 #define FDC_PARK(g, stg)                                                                   \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                          \
+    _Pragma("unroll") for (int j = 0; j < NSRC; ++j)                                       \
         *reinterpret_cast<f32x4*>(&lds[stg][wave + 8 * j][lane]) = g[j]
     // k tile i: rows out of ring stage i % 3, weights out of `b`.  `g` holds the
     // rows of tile i+2 (requested two iterations ago): they go into the stage
     // tile i-1 occupied, and the rows of tile i+4 are requested into `g`.
     // (Reading the row operands of the next tile half way through an iteration, so
     // that none starts with a wait for LDS, measured 4 % slower.)
-    bf16x8 ah[MF], al[MF];
+    uint4 ah[MF], al[MF];
 #define FDC_ROWS(dh, dl, stg_)                                                             \
     _Pragma("unroll") for (int mf = 0; mf < MF; ++mf) {                                    \
-        dh[mf] = __builtin_bit_cast(bf16x8, lds[stg_][MF * wm + mf][lane]);                \
-        dl[mf] = __builtin_bit_cast(bf16x8, lds[stg_][8 + MF * wm + mf][lane]);            \
+        dh[mf] = lds[stg_][MF * wm + mf][lane];                                            \
+        if (!F16) dl[mf] = lds[stg_][(NFA / 2) + MF * wm + mf][lane];                      \
     }
 #define FDC_ITER(g, b, i)                                                                  \
     {                                                                                      \
@@ -297,10 +334,9 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
         FDC_FETCH(g, (i) + 4);                                                             \
         FDC_ROWS(ah, al, stg);                                                             \
         _Pragma("unroll") for (int t = 0; t < TW; ++t) {                                   \
-            const bf16x8 wv = __builtin_bit_cast(bf16x8, b[t]);                            \
             _Pragma("unroll") for (int mf = 0; mf < MF; ++mf) {                            \
-                acc[mf][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, ah[mf], acc[mf][t], 0, 0, 0); \
-                acc[mf][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, al[mf], acc[mf][t], 0, 0, 0); \
+                acc[mf][t] = mma16<F16>(b[t], ah[mf], acc[mf][t]);                         \
+                if (!F16) acc[mf][t] = mma16<F16>(b[t], al[mf], acc[mf][t]);               \
             }                                                                              \
             FDC_FETCHW1(b, t, (i) + NBS);                                                  \
         }                                                                                  \
@@ -357,7 +393,8 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
             for (int t = 0; t < TW; ++t) {
                 const int n = (tile_first + t) * 16 + 4 * (lane >> 4);
                 if (n < a.n_valid)
-                    *reinterpret_cast<f32x4*>(a.out + ((size_t)s * a.M + m) * a.N + n) = acc[mf][t];
+                    *reinterpret_cast<f32x4*>(a.out + ((size_t)s * a.M + m) * a.N + n) =
+                        F16 ? acc[mf][t] * a.out_scale : acc[mf][t];
             }
         }
     } else {
@@ -381,14 +418,13 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
         }
         auto emit = [&](int m, int tile0, const f32x4& gate, const f32x4& upv) {
             if (tile0 + 1 >= p.n_tiles) return;
-            uint16_t hi[4], lo[4];
+            float h[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) split_bf16(gate[e] / (1.0f + __expf(-gate[e])) * upv[e], hi[e], lo[e]);
-            const size_t o = act_frag_index(m, (tile0 >> 1) * 16 + 4 * (lane >> 4), a.out_KT);
-            *reinterpret_cast<uint2*>(a.out_hi + o) =
-                make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
-            *reinterpret_cast<uint2*>(a.out_lo + o) =
-                make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+            for (int e = 0; e < 4; ++e) {
+                const float gt = F16 ? gate[e] * a.out_scale : gate[e], up = F16 ? upv[e] * a.out_scale : upv[e];
+                h[e] = gt / (1.0f + __expf(-gt)) * up;
+            }
+            store_h4(a, act_frag_index(m, (tile0 >> 1) * 16 + 4 * (lane >> 4), a.out_KT), h);
         };
         // pairs of a wavefront with an even index: (0,1), (2,3), ... and, at a seam,
         // (TW-1, the neighbour's 0); with an odd index at a seam: (1,2), (3,4), ...
@@ -412,29 +448,32 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
 // The narrow tile (ntw 4: QKV, O, down at a few hundred rows) measures faster with
 // four wavefronts and 32x32x16 instructions; the wide ones (gate/up, LM head) with
 // eight wavefronts (9-10 %).
-template <int NTW>
+template <int NTW, bool F16>
 void launch_ntw(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
     const dim3 grid(p.grid);
     if (NTW >= 8) {
         if (epilogue == EPI_SWIGLU)
-            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_SWIGLU, 2>), grid, dim3(512), 0, st, a, p);
+            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_SWIGLU, 2, F16>), grid, dim3(512), 0, st, a, p);
         else
-            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_PARTIAL, 2>), grid, dim3(512), 0, st, a, p);
+            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_PARTIAL, 2, F16>), grid, dim3(512), 0, st, a, p);
     } else {
         if (epilogue == EPI_SWIGLU)
-            hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_SWIGLU>), grid, dim3(256), 0, st, a, p);
+            hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_SWIGLU, F16>), grid, dim3(256), 0, st, a, p);
         else
-            hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_PARTIAL>), grid, dim3(256), 0, st, a, p);
+            hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_PARTIAL, F16>), grid, dim3(256), 0, st, a, p);
     }
 }
 
 }  // namespace
 
 bool launch_gemm_tiled(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
-    switch (p.ntw) {
-        case 4: launch_ntw<4>(p, epilogue, a, st); break;
-        case 8: launch_ntw<8>(p, epilogue, a, st); break;
-        case 10: launch_ntw<10>(p, epilogue, a, st); break;
+    switch (p.ntw * 2 + (a.f16 ? 1 : 0)) {
+        case 8: launch_ntw<4, false>(p, epilogue, a, st); break;
+        case 9: launch_ntw<4, true>(p, epilogue, a, st); break;
+        case 16: launch_ntw<8, false>(p, epilogue, a, st); break;
+        case 17: launch_ntw<8, true>(p, epilogue, a, st); break;
+        case 20: launch_ntw<10, false>(p, epilogue, a, st); break;
+        case 21: launch_ntw<10, true>(p, epilogue, a, st); break;
         default: return false;   // no kernel for this width: nothing was launched
     }
     return true;

@@ -8,6 +8,7 @@ namespace fdc {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -18,6 +19,12 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
     return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// float -> fp16 bits, round to nearest even, saturating at the largest finite value
+__device__ __forceinline__ uint16_t f2h(float f) {
+    const float c = fminf(fmaxf(f, -65504.0f), 65504.0f);   // NaN stays NaN
+    return __builtin_bit_cast(uint16_t, (_Float16)(f != f ? f : c));
+}
 
 // split a float into a bf16 head and a bf16 tail with head + tail ~ f to 2^-17
 __device__ __forceinline__ void split_bf16(float f, uint16_t& hi, uint16_t& lo) {

@@ -107,14 +107,22 @@ __global__ __launch_bounds__(NT) void resid_norm_kernel(NormArgs a, StepMeta sm)
         *reinterpret_cast<f32x4*>(a.x + (size_t)m * a.d + k) = v[i];
         if (a.hidden_x) *reinterpret_cast<f32x4*>(a.hidden_x + (size_t)m * a.d + k) = v[i];
         const f32x4 n = v[i] * rstd * gain[i];
-        uint16_t hi[4], lo[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) split_bf16(n[j], hi[j], lo[j]);
         const size_t o = act_frag_index(m, k, KT);           // 4 consecutive k share a fragment lane
-        *reinterpret_cast<uint2*>(a.a_hi + o) =
-            make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
-        *reinterpret_cast<uint2*>(a.a_lo + o) =
-            make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+        if (a.f16) {                                         // one fp16 fragment for the fp16 tiled projections
+            uint16_t h[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) h[j] = f2h(n[j]);
+            *reinterpret_cast<uint2*>(a.a_hi + o) =
+                make_uint2(h[0] | (uint32_t)h[1] << 16, h[2] | (uint32_t)h[3] << 16);
+        } else {
+            uint16_t hi[4], lo[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) split_bf16(n[j], hi[j], lo[j]);
+            *reinterpret_cast<uint2*>(a.a_hi + o) =
+                make_uint2(hi[0] | (uint32_t)hi[1] << 16, hi[2] | (uint32_t)hi[3] << 16);
+            *reinterpret_cast<uint2*>(a.a_lo + o) =
+                make_uint2(lo[0] | (uint32_t)lo[1] << 16, lo[2] | (uint32_t)lo[3] << 16);
+        }
         if (a.hidden_n) *reinterpret_cast<f32x4*>(a.hidden_n + (size_t)m * a.d + k) = n;
     }
 }

@@ -27,7 +27,8 @@ def as_f32(a):
 class Pair:
     """Oracle decoder + GPU context over the same model, template and prefix."""
 
-    def __init__(self, dims, tpl, weights, n_scenes=1, max_branches=None, max_tokens=1, kv_bf16=True):
+    def __init__(self, dims, tpl, weights, n_scenes=1, max_branches=None, max_tokens=1, kv_bf16=True,
+                 f16_weights=None):
         from paper_2602_02864_amd import Context
         self.dims, self.tpl, self.w, self.B = dims, tpl, weights, n_scenes
         self.n_sure = self.n_rows = 0          # rows whose greedy id had to agree / rows compared
@@ -36,7 +37,10 @@ class Pair:
         # the library's cache is bf16: the oracle stores its K/V in that format too
         self.dec = O.OracleDecoder(dims, weights, tpl.prefix_len, tpl.slot_len, tpl.edges, n_scenes,
                                    kv_bf16=kv_bf16)
-        self.ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, n_scenes, self.Rmax, max_tokens)
+        self.ctx = Context(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, n_scenes, self.Rmax, max_tokens,
+                           f16_weights=f16_weights)
+        if f16_weights == "all":
+            self.ctx.set_f16_projections(31)       # every projection single-pass on the fp16 copies
         layers = weights["layers"]
         for l in range(dims.n_layers):
             self.ctx.set_layer_weights(l, layers(l) if callable(layers) else layers[l])
