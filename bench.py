@@ -104,9 +104,16 @@ class Decoder:
             self.ctx = Context(dims, tpl.slot_len, edges, tpl.prefix_len, 1, R, 1, share=weights_of.ctx)
         dev = "cuda"
         self.start = torch.tensor(tpl.start_token, dtype=torch.int32, device=dev)
-        self.idx = [torch.tensor(np.where(bf >= 0, bf, 0), dtype=torch.int64, device=dev) for bf, _ in self.passes]
-        self.sel = [torch.tensor(np.nonzero(bf >= 0)[0], dtype=torch.int64, device=dev) for bf, _ in self.passes]
-        self.fld = [torch.tensor(bf[bf >= 0], dtype=torch.int64, device=dev) for bf, _ in self.passes]
+        # per-pass index tensors as views of three device arrays (three uploads, not three per pass)
+        idx_all = torch.tensor(np.stack([np.where(bf >= 0, bf, 0) for bf, _ in self.passes]), dtype=torch.int64, device=dev)
+        sel_np = [np.nonzero(bf >= 0)[0] for bf, _ in self.passes]
+        fld_np = [bf[bf >= 0] for bf, _ in self.passes]
+        ends = np.cumsum([len(x) for x in sel_np])
+        sel_all = torch.tensor(np.concatenate(sel_np), dtype=torch.int64, device=dev)
+        fld_all = torch.tensor(np.concatenate(fld_np), dtype=torch.int64, device=dev)
+        self.idx = [idx_all[i] for i in range(len(self.passes))]
+        self.sel = [sel_all[e - len(x):e] for x, e in zip(sel_np, ends)]
+        self.fld = [fld_all[e - len(x):e] for x, e in zip(fld_np, ends)]
         self.tok_out = torch.empty(R, dtype=torch.int32, device=dev)
         self.last = self.start.clone()
         self.L = lib()
@@ -114,12 +121,13 @@ class Decoder:
 
     def one(self, i):
         from paper_2602_02864_amd.binding import _p, _check, _stream
+        torch = self.torch
         p = i % len(self.passes)
         if p == 0:
             self.ctx.reset()
             self.last = self.start.clone()
         bf, bo = self.passes[p]
-        tok_in = self.last[self.idx[p]].contiguous()
+        tok_in = torch.index_select(self.last, 0, self.idx[p]) if not os.environ.get("FDC_BENCH_STATIC_TOK") else self.start[:self.R].contiguous()
         _check(self.L.fdc_parallel_decode_step(self.ctx._h, self.R, 1, _p(bf), _p(bo), tok_in.data_ptr(), None,
                                                self.tok_out.data_ptr(), None, None, None, _stream()))
         self.last.index_copy_(0, self.fld[p], self.tok_out.index_select(0, self.sel[p]))
@@ -177,13 +185,15 @@ def run_decode(args, cfg_id):
         dec.one(i)
     ms, tokens, t_wall = dec.timed(K)              # the K timed steps: passes 0 .. K-1 of the schedule
     ms_per_step = ms / K
-    sched = dec.whole_schedule() if K != len(passes) else \
-        {"passes": K, "tokens": tokens, "ms": round(ms, 3), "ms_per_pass": round(ms / K, 4),
-         "tokens_per_s": round(tokens / (ms * 1e-3), 1)}
+    first_k = {"passes": K, "tokens": tokens, "ms": round(ms, 3), "ms_per_pass": round(ms / K, 4),
+               "tokens_per_s": round(tokens / (ms * 1e-3), 1)}
+    # --no-schedule (profiler runs that must stay short): only the K steps are run, and
+    # the line says that its value is not the whole-job rate
+    sched = first_k if K == len(passes) or args.no_schedule else dec.whole_schedule()
 
     # the schedule once more with an event after every pass: the spread of the pass latency
     # (the passes differ: 8, then 3, then 1 ready fields); not part of the timed regions above
-    n_all = len(passes)
+    n_all = K if args.no_schedule else len(passes)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_all + 1)]
     marks[0].record()
     for i in range(n_all):
@@ -191,7 +201,7 @@ def run_decode(args, cfg_id):
         marks[i + 1].record()
     torch.cuda.synchronize()
     per_pass = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_all)])
-    width = np.array([int((bf >= 0).sum()) for bf, _ in passes])
+    width = np.array([int((passes[i % len(passes)][0] >= 0).sum()) for i in range(n_all)])
     spread = {"p10": round(float(np.percentile(per_pass, 10)), 4), "p50": round(float(np.percentile(per_pass, 50)), 4),
               "p90": round(float(np.percentile(per_pass, 90)), 4), "max": round(float(per_pass.max()), 4),
               "by_ready_fields": {str(int(r)): {"passes": int((width == r).sum()),
@@ -228,8 +238,10 @@ def run_decode(args, cfg_id):
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4),
-        "value_basis": f"whole schedule of Algorithm 1: {sched['tokens']} tokens in {sched['passes']} passes, "
-                       f"{sched['ms']} ms; ms_per_step is the mean of the {K} timed steps (passes 0..{K - 1})",
+        "value_basis": (f"whole schedule of Algorithm 1: {sched['tokens']} tokens in {sched['passes']} passes, "
+                        f"{sched['ms']} ms; ms_per_step is the mean of the {K} timed steps (passes 0..{K - 1})")
+        if sched["passes"] == len(passes) else
+        f"FIRST {K} PASSES ONLY (--no-schedule): not the whole-job rate, which needs all {len(passes)} passes",
         "schedule": sched,
         "first_steps": {"steps": K, "tokens": tokens, "tokens_per_step": round(tokens / K, 3),
                         "tokens_per_s": round(tokens / (ms * 1e-3), 1),
@@ -666,10 +678,14 @@ def main():
     ap.add_argument("--no-ar", action="store_true",
                     help="skip the three-graph / autoregressive comparison (Sec. 4.3)")
     ap.add_argument("--no-multi", action="store_true", help="cfg2: skip the 256-row (workload 4) leg")
+    ap.add_argument("--no-schedule", action="store_true",
+                    help="run only the --steps passes (short runs under a profiler); the value is then not the whole-job rate")
     ap.add_argument("--no-driver", action="store_true", help="skip the run of the library's own Algorithm 1 loop")
     ap.add_argument("--prefill", action="store_true", help="also time the causal prefill of the prefix")
     ap.add_argument("--prefill-chunk", type=int, default=1024, help="prefix tokens per prefill pass (at most 1024)")
     ap.add_argument("--single", action="store_true", help="cfg3: only --rho, no sweep over densities")
+    ap.add_argument("--event-overhead-us", type=float, default=None,
+                    help="cost of an event pair around a launch; measured by ~1300 calibration launches when absent")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -683,11 +699,14 @@ def main():
     lib()                                            # fails loudly if the library is not built
     from paper_2602_02864_amd import fdc_profile_calibrate
     # the event pair's cost around a launch of about the dominant kernel's length
-    cal = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
-    fdc_profile_calibrate(20, cal)
-    args.event_overhead_us, cal_us = fdc_profile_calibrate(200, cal)
-    _, null_us = fdc_profile_calibrate(200)
-    del cal
+    if args.event_overhead_us is None:
+        cal = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        fdc_profile_calibrate(20, cal)
+        args.event_overhead_us, cal_us = fdc_profile_calibrate(200, cal)
+        _, null_us = fdc_profile_calibrate(200)
+        del cal
+    else:
+        cal_us = null_us = None          # taken from the command line: no calibration launches
     copy_ref = copy_reference(torch)
     if args.workload == "cfg3":
         # densities 0 and 1 have one graph each; the random ones are drawn --dag-seeds times
@@ -750,7 +769,7 @@ def main():
     elif args.workload == "cfg3" and not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline_attention()
     res["timing"] = {"event_pair_overhead_us": round(args.event_overhead_us, 2),
-                     "calibration_launch_us": round(cal_us, 2), "empty_launch_us": round(null_us, 2),
+                     "calibration_launch_us": cal_us and round(cal_us, 2), "empty_launch_us": null_us and round(null_us, 2),
                      "note": "per-kernel avg_us = event-pair time minus event_pair_overhead_us"}
     res["hbm_copy"] = copy_ref
     print(json.dumps(res), flush=True)

@@ -1,9 +1,9 @@
 """Text summaries of rocprofv3 output (its rocpd SQLite databases).
 
-    python -m paper_2602_02864_amd.rocprof_summary trace   RUN_DIR
-    python -m paper_2602_02864_amd.rocprof_summary traffic FETCH_DIR WRITE_DIR \
+    python bench_rocprof.py trace   RUN_DIR
+    python bench_rocprof.py traffic FETCH_DIR WRITE_DIR \
         --copy-bytes 1073741824 --workload cfg2 --kernel gate_up_swiglu=gemm_skinny_kernel<4, 4, 1> \
-        [--json paper_2602_02864_amd/measured_traffic.json]
+        [--json profiles/hbm_traffic_measured.json]
 
 `trace` prints calls / average / min / max / total per kernel of a
 `rocprofv3 --kernel-trace --stats` run.  `traffic` reads one `--pmc FETCH_SIZE`

@@ -267,17 +267,20 @@ int32_t check_step(const fdc_ctx* c, int R, int T, const int32_t* bf, const int3
 // when the workspace is set (a context can be created and its plan inspected
 // without a GPU)
 int32_t ensure_staging(fdc_ctx* c) {
-    const size_t stage_bytes = sizeof(int32_t) * c->meta_ints;
+    // whole pages: sub-page pinned allocations share pages with other host data
+    const size_t stage_bytes = align_up(sizeof(int32_t) * c->meta_ints, 4096);
     for (int i = 0; i < kStageSlots; ++i) {
         if (!c->stage[i]) FDC_HIP(hipHostMalloc((void**)&c->stage[i], stage_bytes, hipHostMallocDefault));
         if (!c->stage_ev[i]) FDC_HIP(hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming));
     }
-    if (!c->drv_host) FDC_HIP(hipHostMalloc((void**)&c->drv_host, sizeof(int32_t) * 2 * c->Mmax, hipHostMallocDefault));
+    if (!c->drv_host)
+        FDC_HIP(hipHostMalloc((void**)&c->drv_host, align_up(sizeof(int32_t) * 2 * c->Mmax, 4096), hipHostMallocDefault));
     return FDC_OK;
 }
 
-// Copies branch tables + valid_len to the device through the pinned ring and
-// builds the step's visibility words from them.  A call with the tables the
+// Brings branch tables + valid_len to the device through the pinned ring (a
+// one-workgroup kernel reads them from host memory) and builds the step's
+// visibility words and position table from them.  A call with the tables the
 // device already holds (the attention of another layer in the same state, on the
 // same stream) reuses both.
 int32_t upload_meta(fdc_ctx* c, int R, const int32_t* bf, const int32_t* bo, hipStream_t st,
@@ -307,7 +310,7 @@ int32_t upload_meta(fdc_ctx* c, int R, const int32_t* bf, const int32_t* bo, hip
     std::memcpy(h, bf, sizeof(int32_t) * nbr);
     std::memcpy(h + nbr, bo, sizeof(int32_t) * nbr);
     std::memcpy(h + 2 * nbr, c->valid_len.data(), sizeof(int32_t) * c->B * c->F);
-    FDC_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * n, hipMemcpyHostToDevice, st));
+    launch_tables_copy(h, d, (int)n, st);              // the device reads the pinned tables itself
     FDC_HIP(hipEventRecord(c->stage_ev[slot], st));
     c->stage_used[slot] = true;
     launch_mask_words(*sm, c->at<uint64_t>(c->off.anc), c->P, c->NB - c->P / 32,
@@ -1025,7 +1028,7 @@ int32_t fdc_cot_decode(fdc_ctx* c, const int32_t* start_token, const int32_t* fi
                 bo[b] = t0;
                 for (int t = 0; t < T; ++t) h_in[b * T + t] = fixed_tok[fixed_at[f] + t0 + t];
             }
-            FDC_HIP(hipMemcpyAsync(d_in, h_in, sizeof(int32_t) * B * T, hipMemcpyHostToDevice, st));
+            launch_tables_copy(h_in, d_in, B * T, st);
             int32_t rc = fdc_parallel_decode_step(c, 1, T, bf.data(), bo.data(), d_in, nullptr, d_out, nullptr,
                                                   nullptr, nullptr, stream);
             if (rc != FDC_OK) return rc;
@@ -1060,11 +1063,11 @@ int32_t fdc_cot_decode(fdc_ctx* c, const int32_t* start_token, const int32_t* fi
                 bo[(size_t)b * R + i] = on ? po[(size_t)b * c->Rmax + i] : 0;
                 h_in[(size_t)b * R + i] = on ? last[(size_t)b * F + f] : 0;
             }
-        FDC_HIP(hipMemcpyAsync(d_in, h_in, sizeof(int32_t) * B * R, hipMemcpyHostToDevice, st));
+        launch_tables_copy(h_in, d_in, B * R, st);
         int32_t rc = fdc_parallel_decode_step(c, R, 1, bf.data(), bo.data(), d_in, nullptr, d_out, nullptr, nullptr,
                                               nullptr, stream);
         if (rc != FDC_OK) return rc;
-        FDC_HIP(hipMemcpyAsync(h_out, d_out, sizeof(int32_t) * B * R, hipMemcpyDeviceToHost, st));
+        launch_tables_copy(d_out, h_out, B * R, st);         // the device writes the pinned result buffer
         FDC_HIP(hipStreamSynchronize(st));
         // when a field counts as finished (Algorithm 1's test): the model ended
         // the line, or the slot is full (truncation to the fixed length)

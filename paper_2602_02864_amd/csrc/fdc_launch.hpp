@@ -86,6 +86,8 @@ void launch_kv_scatter(const uint16_t* k_new, const uint16_t* v_new, const int32
 void launch_argmax(const float* logits, int M, int V, int64_t ld, int32_t* idx, float* gap,
                    const int32_t* branch_field, int T, hipStream_t st);
 
+// host_tables: pinned host memory (device-readable); n ints into the workspace
+void launch_tables_copy(const int32_t* host_tables, int32_t* dev_tables, int n, hipStream_t st);
 void launch_null(hipStream_t st);
 void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 

@@ -292,6 +292,14 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     }
 }
 
+// The step's small tables (branch fields, offsets, valid lengths) come from pinned
+// host memory, which the device reads directly: one workgroup copies them into
+// the workspace, where every later kernel of the step finds them.
+__global__ __launch_bounds__(256) void tables_copy_kernel(const int32_t* __restrict__ host_tables,
+                                                          int32_t* __restrict__ dev_tables, int n) {
+    for (int i = threadIdx.x; i < n; i += 256) dev_tables[i] = host_tables[i];
+}
+
 // measurement helpers: an empty kernel (what an event pair costs around a
 // launch) and a streaming copy (what the device's HBM sustains, and the
 // reference the traffic counters are scaled by)
@@ -308,6 +316,10 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const copy_u32x4* __re
 }  // namespace
 
 void launch_null(hipStream_t st) { null_kernel<<<1, 64, 0, st>>>(); }
+
+void launch_tables_copy(const int32_t* host_tables, int32_t* dev_tables, int n, hipStream_t st) {
+    if (n > 0) tables_copy_kernel<<<1, 256, 0, st>>>(host_tables, dev_tables, n);
+}
 
 void launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st) {
     const size_t n16 = bytes / 16;
