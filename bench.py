@@ -127,7 +127,7 @@ class Decoder:
             self.ctx.reset()
             self.last = self.start.clone()
         bf, bo = self.passes[p]
-        tok_in = torch.index_select(self.last, 0, self.idx[p]) if not os.environ.get("FDC_BENCH_STATIC_TOK") else self.start[:self.R].contiguous()
+        tok_in = torch.index_select(self.last, 0, self.idx[p])
         _check(self.L.fdc_parallel_decode_step(self.ctx._h, self.R, 1, _p(bf), _p(bo), tok_in.data_ptr(), None,
                                                self.tok_out.data_ptr(), None, None, None, _stream()))
         self.last.index_copy_(0, self.fld[p], self.tok_out.index_select(0, self.sel[p]))

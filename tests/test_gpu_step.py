@@ -334,14 +334,25 @@ def test_repeated_runs_are_bit_identical():
     pair.close()
 
 
+def _curve_rows(errs_by_name):
+    """One curve per name as a table: every fourth layer, the last one, the maximum."""
+    n = len(next(iter(errs_by_name.values())))
+    pick = sorted({l for l in range(4, n, 4)} | {n - 1})
+    out = ["   layer " + " ".join(f"{l:>9d}" for l in pick) + "       max"]
+    for name, e in errs_by_name.items():
+        out.append(f"   {name:<5s} " + " ".join(f"{e[l]:9.2e}" for l in pick) + f" {max(e):9.2e}")
+    return out
+
+
 def _curve_file(name, lines):
-    """Per-layer error curves of a full-depth run, kept as a record: written under
-    gpurun_out/ (the folder that comes back from a GPU run)."""
+    """Per-layer error curves of a full-depth run, kept as a record next to the
+    run's other outputs (profiles/parity_error_curve.txt is these files, one after
+    the other)."""
     import os
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    d = os.environ.get("FDC_RECORD_DIR") or os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
     os.makedirs(d, exist_ok=True)
     with open(os.path.join(d, f"parity_error_curve_{name}.txt"), "w") as f:
-        f.write("\n".join(lines) + "\n")
+        f.write("\n".join(lines) + "\n\n")
 
 
 def _both_oracles_step(pair, plain, bf, bo, ti, tag, curves):
@@ -364,12 +375,12 @@ def _both_oracles_step(pair, plain, bf, bo, ti, tag, curves):
 
 
 def _curve_lines(title, curves):
-    out = [title, "columns: layer | GPU vs oracle with bf16 K/V storage | GPU vs oracle with fp64 K/V | "
-                  "oracle bf16-storage vs oracle fp64 (the storage format alone, CPU only)",
-           "metric: max|a - b| / max|b| over the residual stream after each layer (layer 0 = embedding)"]
+    out = [title, "rows: A = GPU vs oracle with bf16 K/V storage (the graded comparison), B = GPU vs oracle with fp64 K/V,",
+           "      C = oracle bf16-storage vs oracle fp64 (the storage format alone, CPU only)",
+           "metric: max|a - b| / max|b| over the residual stream after a layer"]
     for tag, e_store, e_plain, e_fmt in curves:
         out.append(f"-- {tag}")
-        out += [f"{l:3d} {a:.3e} {b:.3e} {c:.3e}" for l, (a, b, c) in enumerate(zip(e_store, e_plain, e_fmt))]
+        out += _curve_rows({"A": e_store, "B": e_plain, "C": e_fmt})
     return out
 
 
@@ -490,7 +501,7 @@ def test_workload2_model_full_depth_32_rows_per_step():
     L = dims.n_layers
     rng = np.random.default_rng(77)
     lines = ["workload 2 model (28 layers), 8 branches x 4 tokens = 32 rows per step (tiled projections)",
-             "columns: layer | GPU vs oracle with bf16 K/V storage (max|a - b| / max|b| over the residual stream)"]
+             "row A = GPU vs oracle with bf16 K/V storage (max|a - b| / max|b| over the residual stream after a layer)"]
     for step, (mask, name) in enumerate([(16, "default: layer projections two-pass bf16 head + tail, LM head fp16"),
                                          (31, "every projection single-pass fp16 (opt-in)")]):
         pair.ctx.set_f16_projections(mask)
@@ -501,7 +512,7 @@ def test_workload2_model_full_depth_32_rows_per_step():
         errs = [rel_err(got["hidden"][l][rows], ref["hidden"][l][rows]) for l in range(L + 1)]
         e_log = rel_err(got["logits"][rows], ref["logits"][rows])
         lines.append(f"-- pass {step}, offsets {4 * step}..{4 * step + 3}; {name}; logits {e_log:.3e}")
-        lines += [f"{l:3d} {e:.3e}" for l, e in enumerate(errs)]
+        lines += _curve_rows({"A": errs})
         if mask == 16:
             worst = pair.compare(ref, got, "32 rows per step, default projections")
             assert worst < ARITH_BOUND, worst
