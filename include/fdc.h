@@ -370,11 +370,23 @@ int32_t fdc_step_tables_dense(fdc_ctx* ctx, int32_t n_branches, int32_t T,
 /* How a context cuts its attention launches (host only, works without a GPU;
  * for tests of the launch arithmetic).  info[10]: kernel variant, 32-row tiles
  * per row group, row groups at the largest step, key chunks, weighted tiles per
- * chunk, weight of a tile past the prefix in quarters, 32-key tiles in all,
+ * chunk, weight of a tile past the prefix in sixteenths, 32-key tiles in all,
  * tiles that end inside the prefix, the kernel's limit of tiles per chunk, its
  * limit of tiles past the prefix per chunk.  chunk_first_tile [chunks + 1] or
  * NULL: first tile of every chunk, then the end. */
 int32_t fdc_attention_plan(const fdc_ctx* ctx, int32_t* info, int32_t* chunk_first_tile);
+
+/* The same for one step (host only): with many rows per KV head the key chunks
+ * are cut per step, by how many slot tiles the step's rows see at the current
+ * valid_len (tiles nobody sees are skipped by the kernel, so a pass of root
+ * fields and a pass of late fields want different cuts).  Arguments as
+ * fdc_masked_attention's tables; info and chunk_first_tile as above, with the
+ * step's chunk count, weighted tiles per chunk and weight (never more chunks
+ * than the context's plan: chunk_first_tile holds that many + 1 entries).
+ * Contexts whose plan is not cut per step report the context's plan. */
+int32_t fdc_attention_plan_step(fdc_ctx* ctx, int32_t n_branches, int32_t T,
+                                const int32_t* branch_field, const int32_t* branch_off,
+                                int32_t* info, int32_t* chunk_first_tile);
 
 /* Per-row greedy argmax over fp32 logits (final logits are fp32, Sec. 4.1).
  * logits device [M][ld] (ld >= V); idx_out device int32 [M]: lowest index of

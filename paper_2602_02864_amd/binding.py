@@ -33,7 +33,7 @@ EXPORTS = [
     "fdc_profile_calibrate", "fdc_stream_copy",
     "fdc_sched_create", "fdc_sched_next", "fdc_sched_destroy",
     "fdc_sched_peek", "fdc_sched_advance", "fdc_sched_complete", "fdc_sched_stats",
-    "fdc_cot_decode", "fdc_step_tables_dense", "fdc_attention_plan",
+    "fdc_cot_decode", "fdc_step_tables_dense", "fdc_attention_plan", "fdc_attention_plan_step",
     "fdc_set_layer_weights_f16", "fdc_set_head_weights_f16", "fdc_set_f16_projections",
 ]
 FDC_PROF_KINDS = 9
@@ -161,6 +161,8 @@ def lib() -> C.CDLL:
     L.fdc_step_tables_dense.argtypes = [vp, i32, i32, pi32, pi32, C.POINTER(C.c_uint8), pi32, vp]
     L.fdc_attention_plan.restype = i32
     L.fdc_attention_plan.argtypes = [vp, pi32, pi32]
+    L.fdc_attention_plan_step.restype = i32
+    L.fdc_attention_plan_step.argtypes = [vp, i32, i32, pi32, pi32, pi32, pi32]
     _lib = L
     return L
 
@@ -351,8 +353,10 @@ def fdc_stream_copy(dst, src) -> None:
     _check(lib().fdc_stream_copy(dst.data_ptr(), src.data_ptr(), nb, _stream()))
 
 
-def fdc_attention_plan(dims, slot_len, edges, prefix_len, n_scenes=1, max_branches=1, max_tokens=1) -> dict:
-    """The attention launch plan of a context of this shape (host only: no GPU needed)."""
+def fdc_attention_plan(dims, slot_len, edges, prefix_len, n_scenes=1, max_branches=1, max_tokens=1,
+                       step=None) -> dict:
+    """The attention launch plan of a context of this shape (host only: no GPU needed).
+    step = (valid_len [B][F], branch_field, branch_off, T): the cut of that step."""
     desc = ModelDesc(dims.n_layers, dims.d_model, dims.n_q_heads, dims.n_kv_heads, dims.head_dim,
                      dims.d_mlp, dims.vocab, dims.rope_base, dims.norm_eps)
     sl = _i32(slot_len)
@@ -364,7 +368,14 @@ def fdc_attention_plan(dims, slot_len, edges, prefix_len, n_scenes=1, max_branch
         info = np.zeros(10, dtype=np.int32)
         _check(lib().fdc_attention_plan(h, _p(info), None))
         first = np.zeros(int(info[3]) + 1, dtype=np.int32)
-        _check(lib().fdc_attention_plan(h, _p(info), _p(first)))
+        if step is None:
+            _check(lib().fdc_attention_plan(h, _p(info), _p(first)))
+        else:
+            vl, bf, bo, T = step
+            vl, bf, bo = _i32(vl), _i32(bf), _i32(bo)
+            _check(lib().fdc_set_valid_len(h, _p(vl)))
+            _check(lib().fdc_attention_plan_step(h, bf.size // n_scenes, int(T), _p(bf), _p(bo), _p(info), _p(first)))
+            first = first[:int(info[3]) + 1]
     finally:
         lib().fdc_destroy(h)
     keys = ("variant", "nrt", "rg_max", "chunks", "cb", "wq", "tiles", "prefix_tiles", "max_chunk_tiles",

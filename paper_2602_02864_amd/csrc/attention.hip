@@ -44,6 +44,7 @@ constexpr float kNegBig = -1.0e30f;     // score of a masked key
 // exponent stays hugely negative and its weight is exactly 0 without a second
 // masking pass, also for a row that has seen no visible key yet.
 constexpr float kMaxFloor = -1.0e20f;
+constexpr float kLazy = 8.0f;
 
 // score or kNegBig by visibility bit k of `bits`, without a compare
 __device__ __forceinline__ float keep_if(float x, uint32_t bits, int k) {
@@ -112,6 +113,25 @@ __device__ __forceinline__ uint32_t lds_off(const void* p) {
 }
 __device__ __forceinline__ void lds_read128(Frag& f, uint32_t off) {
     asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(off));
+}
+template <int OFF>
+__device__ __forceinline__ void lds_read128_at(Frag& f, uint32_t base) {   // OFF: immediate byte offset
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.v) : "v"(base), "n"(OFF));
+}
+// the DJ 1 KiB fragments of one K or V tile, one address register for all of them
+template <int DJ>
+__device__ __forceinline__ void read_frags(Frag (&fr)[DJ], uint32_t base) {
+    static_assert(DJ == 8 || DJ == 4, "head sizes 128 and 64");
+    lds_read128_at<0>(fr[0], base);
+    lds_read128_at<1024>(fr[1], base);
+    lds_read128_at<2048>(fr[2], base);
+    lds_read128_at<3072>(fr[3], base);
+    if (DJ == 8) {
+        lds_read128_at<4096>(fr[4 % DJ], base);
+        lds_read128_at<5120>(fr[5 % DJ], base);
+        lds_read128_at<6144>(fr[6 % DJ], base);
+        lds_read128_at<7168>(fr[7 % DJ], base);
+    }
 }
 __device__ __forceinline__ uint32_t lds_read32(uint32_t off) {
     uint32_t v;
@@ -230,12 +250,31 @@ __device__ __forceinline__ void build_tables_direct(const AttnArgs& a, const Ste
         row_head[r] = ri.head;
     }
     __syncthreads();
-    for (int idx = tid; idx < nmt * NR; idx += NT) {
-        const int t = idx / NR, r = idx % NR;
-        const int jr = (rg * NR + r) / a.G;
-        const uint32_t bits = (row_m[r] >= 0 && jr < RT) ? words[(size_t)t * RT + jr] : 0u;
-        rowmask[t][r] = bits;
-        if (bits) atomicOr(&tile_any[t], bits);
+    // one row per thread, NT / NR threads to a row, every TS-th tile each: all words
+    // of a thread are requested before the first is used (one memory latency, not
+    // one per tile)
+    static_assert(NT % NR == 0 && NR % 64 == 0, "whole threads per row, whole wavefronts per tile");
+    constexpr int TS = NT / NR, PER = (kMaxMaskedTiles + TS - 1) / TS;
+    const int r = tid % NR, tq = tid / NR;
+    const int jr = (rg * NR + r) / a.G;
+    const bool row_ok = row_m[r] >= 0 && jr < RT;
+    uint32_t bits[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int t = tq + k * TS;
+        bits[k] = (row_ok && t < nmt) ? words[(size_t)t * RT + jr] : 0u;
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int t = tq + k * TS;
+        if (t < nmt) {                                      // the same tile for the whole wavefront
+            rowmask[t][r] = bits[k];
+            // one atomic per wavefront: 64 lanes on one LDS word would take turns
+            uint32_t v = bits[k];
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) v |= (uint32_t)__shfl_xor((int)v, o);
+            if ((tid & 63) == 0 && v) atomicOr(&tile_any[t], v);
+        }
     }
     __syncthreads();
 }
@@ -589,6 +628,26 @@ __global__ __launch_bounds__(NRT * 64, 2) void attn_partial_wide_kernel(AttnArgs
         }
     }
 
+    // Tiles of the prefix are visible to every row: when the chunk starts with kDist
+    // of them their copies leave now, under the table set-up, not after it.
+    const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
+    const uint32_t lane_off = (uint32_t)lane * 8;           // bf16 elements
+    auto issue_tile = [&](int blk, int stg) {               // blk, stg: scalar
+        const size_t toff = (tile_base + blk) * TILE;
+#pragma unroll
+        for (int p = 0; p < LPW; ++p) {
+            const int piece = rt * LPW + p;                 // < DJ: K, else V (scalar)
+            const uint16_t* base = (piece < DJ ? a.kc : a.vc) + toff + (piece % DJ) * 512;
+            uint16_t* dst = &stage[stg][piece * 512];
+            __builtin_amdgcn_global_load_lds((glb_void*)(base + lane_off), (lds_void*)dst, 16, 0, 2 /* nt: streamed once */);
+        }
+    };
+    const bool early = cb0 + kDist <= min(mt0, blk_end);
+    if (early && rt < NISS) {
+#pragma unroll
+        for (int i = 0; i < kDist; ++i) issue_tile(cb0 + i, i);
+    }
+
     build_tables_direct<NR, NT>(a, sm, b, kvh, rg, mt0, nmt, row_m, row_head, rowmask, tile_any);
     if (rt == 0) {
         const int blk = cb0 + lane;                         // at most 64 tiles per chunk
@@ -622,25 +681,18 @@ __global__ __launch_bounds__(NRT * 64, 2) void attn_partial_wide_kernel(AttnArgs
             qh[j].v = row_act ? qb[j] : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
         }
     }
-    // no load of the set-up may be counted among the tile copies below
+    // no load of the set-up may be counted among the tile copies below (copies that
+    // left early have landed by then, which the loop's waits allow for)
     __builtin_amdgcn_s_waitcnt(0);
 
-    const size_t tile_base = ((size_t)b * a.Hkv + kvh) * a.NB;
-    const uint32_t lane_off = (uint32_t)lane * 8;           // bf16 elements
     auto issue = [&](int i, int stg) {
         if (i >= n_act || rt >= NISS) return;
-        const int blk = __builtin_amdgcn_readlane(my_tiles, i);
-        const size_t toff = (tile_base + blk) * TILE;       // scalar
-#pragma unroll
-        for (int p = 0; p < LPW; ++p) {
-            const int piece = rt * LPW + p;                 // < DJ: K, else V (scalar)
-            const uint16_t* base = (piece < DJ ? a.kc : a.vc) + toff + (piece % DJ) * 512;
-            uint16_t* dst = &stage[stg][piece * 512];
-            __builtin_amdgcn_global_load_lds((glb_void*)(base + lane_off), (lds_void*)dst, 16, 0, 2 /* nt: streamed once */);
-        }
+        issue_tile(__builtin_amdgcn_readlane(my_tiles, i), stg);
     };
+    if (!early) {
 #pragma unroll
-    for (int i = 0; i < kDist; ++i) issue(i, i);
+        for (int i = 0; i < kDist; ++i) issue(i, i);
+    }
 
     f32x16 o[DT];
     float m_run = kMaxFloor, l_run = 0.f;
@@ -655,35 +707,29 @@ __global__ __launch_bounds__(NRT * 64, 2) void attn_partial_wide_kernel(AttnArgs
     // One 32-key tile against this wavefront's 32 rows, in two phases: scores
     // (S^T = K * Q^T into `sc`), then softmax and O^T += V^T * P^T.  The eight
     // fragments of K and then the eight of V pass through the same registers.
-    // Two independent accumulators (query heads, query tails), so that consecutive
-    // matrix instructions never wait for each other's result; summed afterwards.
+    // Query heads and tails accumulate into the same registers: the other wavefront
+    // of the SIMD fills the gaps between dependent matrix instructions.
     f32x16 sc;
     auto scores = [&](int stg) {
         const uint32_t ks = stage_off + stg * (4 * TILE);   // bytes
         Frag fr[DJ];
+        read_frags<DJ>(fr, ks);
 #pragma unroll
-        for (int j = 0; j < DJ; ++j) lds_read128(fr[j], ks + j * 1024);
-        f32x16 st;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) sc[k] = st[k] = 0.f;
+        for (int k = 0; k < 16; ++k) sc[k] = 0.f;
         constexpr int HJ = DJ / 2;
         asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(HJ) : "memory");
 #pragma unroll
         for (int j = 0; j < HJ; ++j) {
             asm volatile("" : "+v"(fr[j].v));
             sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, qh[j].v, sc, 0, 0, 0);
-            if (QF32) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, ql[j].v, st, 0, 0, 0);
+            if (QF32) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, ql[j].v, sc, 0, 0, 0);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
         for (int j = HJ; j < DJ; ++j) {
             asm volatile("" : "+v"(fr[j].v));
             sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, qh[j].v, sc, 0, 0, 0);
-            if (QF32) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, ql[j].v, st, 0, 0, 0);
-        }
-        if (QF32) {
-#pragma unroll
-            for (int k = 0; k < 16; ++k) sc[k] += st[k];
+            if (QF32) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j].v, ql[j].v, sc, 0, 0, 0);
         }
     };
     auto softmax_pv = [&](int stg, int blk) {
@@ -694,8 +740,7 @@ __global__ __launch_bounds__(NRT * 64, 2) void attn_partial_wide_kernel(AttnArgs
         // the V fragments are requested now and consumed after the softmax:
         // fragment dt*2 + s2 of the V half of the stage
         Frag fr[DJ];
-#pragma unroll
-        for (int j = 0; j < DJ; ++j) lds_read128(fr[j], vs + j * 1024);
+        read_frags<DJ>(fr, vs);
         if (masked) {
             uint32_t w0 = lds_read32(rowmask_off + (blk - mt0) * (NR * 4));
             uint32_t w1 = lds_read32(any_off + (blk - mt0) * 4);
@@ -710,7 +755,12 @@ __global__ __launch_bounds__(NRT * 64, 2) void attn_partial_wide_kernel(AttnArgs
 #pragma unroll
         for (int k = 0; k < 16; ++k) mx = fmaxf(mx, sc[k]);
         mx = fmaxf(mx, other_half(mx, hh));
-        const float m_new = fmaxf(m_run, mx * a.scale_log2);
+        float m_new = fmaxf(m_run, mx * a.scale_log2);
+        // the reference point of the exponentials moves only when a score exceeds it by
+        // more than 2^kLazy: weights then stay below 2^kLazy (no loss in fp32 or in the
+        // head + tail pair), and the rescaling of the 64 accumulator registers is skipped
+        // for almost every tile after a chunk's first
+        if (m_new - m_run <= kLazy) m_new = m_run;
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         m_run = m_new;
         float psum = 0.f;

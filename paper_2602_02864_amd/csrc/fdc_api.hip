@@ -49,7 +49,8 @@ struct fdc_ctx {
     int Mp = kMaxRowsDense;              // rows the workspace is laid out for (multiple of 16)
 
     // attention launch shape for the largest step
-    int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1, attn_variant = 0, attn_wq = 4;
+    int attn_nrt = 1, attn_rg_max = 1, attn_cb = 4, attn_chunks = 1, attn_variant = 0, attn_wq = 16;
+    int step_cb = 0, step_wq = 0, step_chunks = 0;   // this step's chunk cut (many-row kernel); 0: the context's
 
     // workspace
     char* ws = nullptr;
@@ -127,8 +128,8 @@ void plan_attention(fdc_ctx* c) {
         // tiles past the prefix carry masks and measure about 1.5 plain tiles each:
         // chunks are cut equal in weighted tiles, or the chunk with the slots would
         // finish long after the others
-        c->attn_wq = 6;
-        const long total = t0 + (masked_total * c->attn_wq + 3) / 4;
+        c->attn_wq = 24;
+        const long total = t0 + (masked_total * c->attn_wq + 15) / 16;
         const long zr = (long)c->B * c->m.n_kv_heads * c->attn_rg_max;
         long want_wgs = c->attn_nrt == 8 ? 256 : 512;      // four-wavefront workgroups run two to a compute unit
         if (const char* e = std::getenv("FDC_ATTN_WGS")) want_wgs = std::max(1L, std::atol(e));
@@ -160,8 +161,8 @@ void plan_attention(fdc_ctx* c) {
         // each (table set-up included): chunks are cut equal in weighted tiles.
         // Whole rounds of workgroups over the compute units: the cheapest of
         // (rounds) x (weighted tiles per chunk + a fixed set-up and merge cost).
-        c->attn_wq = 6;
-        total = t0 + (masked_total * c->attn_wq + 3) / 4;
+        c->attn_wq = 24;
+        total = t0 + (masked_total * c->attn_wq + 15) / 16;
         long best = 0, best_cost = 0;
         for (long ch = 1; ch <= std::max(1L, total / 8); ++ch) {
             const long t = (total + ch - 1) / ch;
@@ -322,6 +323,57 @@ int32_t upload_meta(fdc_ctx* c, int R, const int32_t* bf, const int32_t* bo, hip
     return FDC_OK;
 }
 
+// The many-row kernel skips slot tiles that no row of the step sees, so what a
+// slot tile costs on average depends on the step: a pass of root fields touches one
+// tile per branch, a pass of late fields nearly all of them.  The chunk cut weights
+// a slot tile by wq / 16 plain tiles (attn_chunk_start); here wq is set from the
+// step's own count of visible slot tiles (largest over the scenes; a visible one
+// measures 1.2 plain tiles, plus about one tile's time of table set-up in the
+// chunk that has them), with the chunk count the workspace was carved for.  A cut that would
+// overflow a workgroup's tile list or mask table keeps the context's.
+void balance_chunks(fdc_ctx* c, int R, int T, const int32_t* bf, const int32_t* bo) {
+    c->step_cb = c->step_wq = c->step_chunks = 0;
+    if (c->attn_variant != 2) return;
+    const int t0 = c->P / 32, masked_total = c->NB - t0;
+    if (masked_total <= 0) return;
+    std::vector<uint8_t> seen((size_t)masked_total);
+    int most = 0;
+    for (int b = 0; b < c->B; ++b) {
+        std::fill(seen.begin(), seen.end(), 0);
+        auto mark = [&](int g, int len) {
+            if (len <= 0) return;
+            const int p0 = c->slot_start[g], p1 = p0 + len - 1;
+            for (int t = p0 / 32; t <= p1 / 32; ++t) seen[t - t0] = 1;
+        };
+        for (int r = 0; r < R; ++r) {
+            const int f = bf[b * R + r];
+            if (f < 0) continue;
+            mark(f, bo[b * R + r] + T);
+            for (int g = 0; g < c->F; ++g)
+                if (c->anc[f] >> g & 1) mark(g, c->valid_len[(size_t)b * c->F + g]);
+        }
+        int n = 0;
+        for (uint8_t v : seen) n += v;
+        most = std::max(most, n);
+    }
+    const double weight = 1.2 * most + 1.0;
+    const int wq = (int)std::min(32.0, std::max(2.0, std::floor(16.0 * weight / masked_total + 0.5)));
+    const long total = t0 + ((long)masked_total * wq + 15) / 16;
+    long cb = (total + c->attn_chunks - 1) / c->attn_chunks;
+    cb = std::max(4L, cb);
+    const int chunks = (int)((total + cb - 1) / cb);
+    if (chunks > c->attn_chunks) return;
+    for (int ch = 0; ch < chunks; ++ch) {
+        const int a0 = attn_chunk_start(c->P, c->NB, (int)cb, wq, ch);
+        const int a1 = std::min(c->NB, attn_chunk_start(c->P, c->NB, (int)cb, wq, ch + 1));
+        if (a1 - a0 > kMaxChunkTilesWide || a1 - std::max(a0, t0) > kMaxMaskedTiles) return;
+    }
+    if (attn_chunk_start(c->P, c->NB, (int)cb, wq, chunks) < c->NB) return;
+    c->step_cb = (int)cb;
+    c->step_wq = wq;
+    c->step_chunks = chunks;
+}
+
 void fill_attn(const fdc_ctx* c, int layer, int R, int T, AttnArgs* a) {
     const fdc_model_desc& m = c->m;
     const int G = m.n_q_heads / m.n_kv_heads;
@@ -339,9 +391,9 @@ void fill_attn(const fdc_ctx* c, int layer, int R, int T, AttnArgs* a) {
     a->D = m.head_dim;
     a->P = c->P;
     a->NB = c->NB;
-    a->CB = c->attn_cb;
-    a->wq = c->attn_wq;
-    a->n_chunks = c->attn_chunks;
+    a->CB = c->step_cb ? c->step_cb : c->attn_cb;
+    a->wq = c->step_cb ? c->step_wq : c->attn_wq;
+    a->n_chunks = c->step_cb ? c->step_chunks : c->attn_chunks;
     a->nrt = c->attn_nrt;
     a->variant = c->attn_variant;
     const int NR = a->nrt * 32;
@@ -692,6 +744,25 @@ int32_t fdc_attention_plan(const fdc_ctx* c, int32_t* info, int32_t* chunk_first
     return FDC_OK;
 }
 
+int32_t fdc_attention_plan_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t* bf, const int32_t* bo,
+                                int32_t* info, int32_t* chunk_first_tile) {
+    if (!c || !info) return fail(FDC_EINVAL, "null pointer argument");
+    int32_t rc = check_step(c, R, T, bf, bo, false);
+    if (rc != FDC_OK) return rc;
+    rc = fdc_attention_plan(c, info, nullptr);
+    if (rc != FDC_OK) return rc;
+    balance_chunks(c, R, T, bf, bo);
+    if (c->step_cb) {
+        info[3] = c->step_chunks;
+        info[4] = c->step_cb;
+        info[5] = c->step_wq;
+    }
+    if (chunk_first_tile)
+        for (int ch = 0; ch <= info[3]; ++ch)
+            chunk_first_tile[ch] = attn_chunk_start(c->P, c->NB, info[4], info[5], ch);
+    return FDC_OK;
+}
+
 int32_t fdc_step_tables_dense(fdc_ctx* c, int32_t R, int32_t T, const int32_t* bf, const int32_t* bo,
                               uint8_t* mask, int32_t* pos, void* stream) {
     if (!c || !mask || !pos) return fail(FDC_EINVAL, "null pointer argument");
@@ -753,6 +824,7 @@ int32_t fdc_masked_attention(fdc_ctx* c, int32_t layer, const void* q, int32_t R
     rc = upload_meta(c, R, bf, bo, st, &sm, T);
     if (rc != FDC_OK) return rc;
     AttnArgs a;
+    balance_chunks(c, R, T, bf, bo);
     fill_attn(c, layer, R, T, &a);
     a.q_bf16 = (const uint16_t*)q;
     a.out_f32 = out;
@@ -796,6 +868,7 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
         c->valid_len = saved;
         return rc;
     }
+    balance_chunks(c, R, T, bf, bo);
 
     const int d = m.d_model, HqD = m.n_q_heads * m.head_dim;
     const int Nqkv = HqD + 2 * m.n_kv_heads * m.head_dim;

@@ -106,7 +106,7 @@ struct AttnArgs {
     uint16_t* out_lo;         //     or (out_f16) single fp16 fragments in out_hi
     bool out_f16;
     int Hq, Hkv, G, D, P, NB, CB, n_chunks, n_rg, nrt;   // CB: weighted tiles per chunk
-    int wq;                   // weight of a tile past the prefix, in quarters of a prefix tile
+    int wq;                   // weight of a tile past the prefix, in sixteenths of a prefix tile
     int variant;              // 0: LDS-shared tiles (direct-to-LDS ring), 1: tiles in registers
     float scale_log2;         // log2(e) / sqrt(D)
 };
@@ -119,13 +119,13 @@ void launch_mask_words(const StepMeta& sm, const uint64_t* anc, int P, int n_til
 // First 32-key tile of key chunk c of an attention launch.  Tiles that reach past
 // the prefix carry masks and cost more (measured: about 1.5 plain tiles each,
 // their table set-up included), so chunks are equal in weighted tiles: a tile
-// past the prefix counts wq / 4.  P: prefix length, NB: tiles in all, CB:
+// past the prefix counts wq / 16.  P: prefix length, NB: tiles in all, CB:
 // weighted tiles per chunk.
 __host__ __device__ inline int attn_chunk_start(int P, int NB, int CB, int wq, int c) {
     const int t0 = P >> 5;
     const long x = (long)c * CB;
     if (x <= t0) return (int)x;
-    const long t = t0 + (4 * (x - t0) + wq - 1) / wq;
+    const long t = t0 + (16 * (x - t0) + wq - 1) / wq;
     return (int)(t < NB ? t : NB);
 }
 

@@ -274,7 +274,7 @@ def _check_plan(dims, tpl, B, R, T, tag):
     N = tpl.prefix_len + sum(tpl.slot_len)
     assert p["tiles"] == (N + 31) // 32 and p["prefix_tiles"] == tpl.prefix_len // 32, tag
     assert len(first) == p["chunks"] + 1 and first[0] == 0 and first[-1] == p["tiles"], (tag, p)
-    assert p["wq"] >= 4 and p["nrt"] in (1, 2, 4, 8) and p["rg_max"] >= 1, (tag, p)
+    assert p["wq"] >= 16 and p["nrt"] in (1, 2, 4, 8) and p["rg_max"] >= 1, (tag, p)
     rows = R * T * (dims.n_q_heads // dims.n_kv_heads)
     assert p["rg_max"] * p["nrt"] * 32 >= rows, (tag, p)
     for c in range(p["chunks"]):
@@ -318,6 +318,54 @@ def test_attention_plan_bounds_over_the_admissible_shapes(monkeypatch):
     for cfg, B, R, T in [(0, 1, 3, 1), (1, 1, 6, 1), (2, 1, 8, 1), (3, 16, 16, 1), (4, 8, 8, 4), (4, 8, 32, 4)]:
         t = template(cfg)
         _check_plan(model_dims(cfg), t, B, R, T, f"cfg{cfg}")
+
+
+def test_attention_plan_of_a_step_balances_the_chunks_and_keeps_the_bounds():
+    """With many rows per KV head the key chunks are cut per step.  Workload 4, every
+    level of the template and several slot offsets: the cut covers all tiles, keeps
+    the kernel's limits, has no more chunks than the context's plan, and the chunk
+    that holds the slots has about as many VISIBLE tiles (plus its table set-up) as
+    the others - with the context's fixed cut it had as few as a quarter."""
+    from paper_2602_02864_amd import fdc_attention_plan
+    from synth_inputs import model_dims
+    dims, tpl = model_dims(4), template(4)
+    F, S, B, T = tpl.n_fields, tpl.slot_len[0], 8, 4
+    anc = [set() for _ in range(F)]
+    for s, d in tpl.edges:
+        anc[d].add(s)
+    for _ in range(F):
+        for f in range(F):
+            for g in list(anc[f]):
+                anc[f] |= anc[g]
+    for R, levels in [(8, range(F // 8)), (F, [None])]:
+        base = fdc_attention_plan(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T)
+        for lv in levels:
+            for off in (0, 12, 28):
+                fields = list(range(F)) if lv is None else list(range(8 * lv, 8 * lv + 8))
+                vl = np.zeros((B, F), dtype=np.int32)
+                if lv is not None:
+                    vl[:, :8 * lv] = S
+                vl[:, fields] = off + T
+                bf = np.tile(np.array(fields, dtype=np.int32), B)
+                bo = np.full(bf.size, off, dtype=np.int32)
+                p = fdc_attention_plan(dims, tpl.slot_len, tpl.edges, tpl.prefix_len, B, R, T, step=(vl, bf, bo, T))
+                first, t0 = p["chunk_first_tile"], p["prefix_tiles"]
+                assert p["chunks"] <= base["chunks"] and first[0] == 0 and first[-1] == p["tiles"], (lv, off, p)
+                seen = set()
+                for f in fields:
+                    for g in anc[f] | {f}:
+                        n = off + T if g == f else int(vl[0, g])
+                        if n > 0:
+                            p0 = tpl.prefix_len + sum(tpl.slot_len[:g])
+                            seen |= set(range(p0 // 32, (p0 + n - 1) // 32 + 1))
+                cost = []
+                for c in range(p["chunks"]):
+                    n = first[c + 1] - first[c]
+                    masked = max(0, first[c + 1] - max(first[c], t0))
+                    assert 0 < n <= p["max_chunk_tiles"] and masked <= p["max_masked_tiles"], (lv, off, c, p)
+                    vis = sum(1 for t in range(max(first[c], t0), first[c + 1]) if t in seen)
+                    cost.append((n - masked) + 1.2 * vis + (1 if vis else 0))
+                assert max(cost) <= 1.12 * (sum(cost) / len(cost)) + 1, (lv, off, cost, p)
 
 
 def test_create_refuses_more_cache_positions_than_the_kernels_index():
