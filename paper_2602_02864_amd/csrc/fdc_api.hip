@@ -456,13 +456,17 @@ TiledPlan plan_tiled(int M, int64_t n_out, int64_t k_in, bool swiglu, int max_sp
             const int n_groups = (n_tiles + 2 * ntw - 1) / (2 * ntw);
             const long tasks = (long)n_groups * m_blocks * Seff;
             const long rounds = (tasks + 255) / 256;
-            // clocks of one workgroup: per k tile the matrix pipe (8 * ntw instructions
-            // of 16 clocks per wavefront) or the LDS reads (four wavefronts, 8 + ntw
-            // fragments of 1 KiB each at 128 B per clock), plus a fixed ramp; the
-            // partials of a split cost their write and their read by the consumer
-            const double per_kt = std::max(128.0 * ntw, 32.0 * (8 + ntw));
-            const double partials = Seff > 1 ? 8.0 * Seff * M * (double)n_out / 4.0e12 * 2.4e9 : 0.0;
-            const double cost = rounds * (kts * per_kt + 4000.0) + partials;
+            // Clocks of one workgroup, fitted to measurements of the 7B-class projections
+            // at 256 and 1024 rows (the kernels are bound by the requests a compute unit
+            // keeps in flight, not by the matrix pipe): a fixed part (launch, ramp,
+            // epilogue) plus a cost per k tile - 1080 for the 128-wide tile; 2040 (up to
+            // 256 rows) or 1820 for the 256-wide one, whose weight fragments go to two
+            // wavefronts each; 2290 for the 320-wide one.  Every split writes its partial
+            // and the consumer reads it: 3e-3 clocks per element and split, measured.
+            const double fixed = ntw == 4 ? 19000.0 : 15000.0;
+            const double per_kt = ntw == 4 ? 1080.0 : ntw == 8 ? (m_blocks <= 2 ? 2040.0 : 1820.0) : 2290.0;
+            const double partials = Seff > 1 ? 3.0e-3 * Seff * M * (double)n_out : 0.0;
+            const double cost = rounds * (kts * per_kt + fixed) + partials;
             if (best.grid == 0 || cost < best_cost) {
                 best_cost = cost;
                 best.KT = KT;
