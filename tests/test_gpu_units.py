@@ -63,8 +63,11 @@ def test_argmax_lowest_index_and_gap():
     assert np.array_equal(idx2.cpu().numpy(), np.argmax(lg[:, :1000], axis=1))
 
 
-def _attention_case(dims, tpl, B, T, seed, active_prob=0.8, valid_mode="random"):
-    """Random K/V/q of bf16 values, random cache state; returns max rel err."""
+def _attention_case(dims, tpl, B, T, seed, active_prob=0.8, valid_mode="random", ramp=0.0):
+    """Random K/V/q of bf16 values, random cache state; returns max rel err.
+    ramp > 0: keys and queries share a direction along which the keys grow with their
+    position, so the scores rise steadily through the cache (by `ramp` in all): the
+    running maximum of the softmax keeps moving, far beyond any fixed head-room."""
     torch = _torch()
     from paper_2602_02864_amd import Context
     rng = np.random.default_rng(seed)
@@ -74,6 +77,12 @@ def _attention_case(dims, tpl, B, T, seed, active_prob=0.8, valid_mode="random")
     G = Hq // Hkv
     K = draw_normal_bf16(rng, (B, Hkv, N, D))
     V = draw_normal_bf16(rng, (B, Hkv, N, D))
+    u = None
+    if ramp:
+        from synth_inputs import bf16_round
+        u = rng.standard_normal(D)
+        u /= np.linalg.norm(u)
+        K = bf16_round(K + (ramp * np.sqrt(D) * np.arange(N) / N)[None, None, :, None] * u)
     # cache state: how many tokens of each field exist per scene
     valid = np.zeros((B, F), dtype=np.int32)
     bf = np.full((B, F), -1, dtype=np.int32)
@@ -113,6 +122,8 @@ def _attention_case(dims, tpl, B, T, seed, active_prob=0.8, valid_mode="random")
     ctx.set_valid_len(valid)
     M = B * F * T
     q = draw_normal_bf16(rng, (M, Hq, D))
+    if ramp:
+        q = bf16_round(q + u)
     out = ctx.masked_attention(0, q, bf, bo, T=T)
     torch.cuda.synchronize()
     got = out.cpu().numpy().reshape(M, Hq, D)
@@ -179,6 +190,27 @@ def test_masked_attention_register_variant_on_small_ragged_shapes(monkeypatch, n
     dims = ATT_DIMS[name]
     tpl = random_dag_template(500 + seed, F, P, max_slot, p, dims.vocab)
     err = _attention_case(dims, tpl, B, T, seed)
+    assert err < 2e-3, err
+
+
+@pytest.mark.parametrize("name,seed,F,P,max_slot,p,B,T,ramp", [
+    ("g7d128", 21, 12, 300, 64, 0.3, 2, 4, 0.0),     # 12 x 4 x 7 = 336 rows per KV head: two row groups of eight tiles
+    ("g4d128", 22, 16, 2100, 33, 0.2, 3, 2, 0.0),    # 128 rows: four-wavefront workgroups, long ragged prefix
+    ("g7d64", 23, 10, 515, 20, 0.6, 2, 2, 0.0),      # head size 64
+    ("g7d128", 24, 9, 4000, 40, 0.4, 1, 4, 60.0),    # scores rise by 60 along the cache
+    ("g4d128", 25, 6, 1500, 64, 1.0, 2, 8, 25.0),
+])
+def test_masked_attention_many_rows_kernel_on_ragged_shapes(monkeypatch, name, seed, F, P, max_slot, p, B, T, ramp):
+    """The kernel for many rows per KV head (one workgroup shares each K/V tile among
+    up to eight row tiles), forced onto ragged cases: inactive rows, unwritten
+    positions, T > 1, chunks cut per step; and with scores that keep rising along the
+    cache, so that the reference point of its exponentials (moved only when a score
+    exceeds it by 2^8) moves many times in every chunk and the weights in between
+    are far above 1."""
+    monkeypatch.setenv("FDC_ATTN_VARIANT", "2")
+    dims = ATT_DIMS[name]
+    tpl = random_dag_template(500 + seed, F, P, max_slot, p, dims.vocab)
+    err = _attention_case(dims, tpl, B, T, seed, active_prob=0.9, ramp=ramp)
     assert err < 2e-3, err
 
 
