@@ -4,6 +4,7 @@
     python bench_rocprof.py traffic FETCH_DIR WRITE_DIR \
         --copy-bytes 1073741824 --workload cfg2 --kernel gate_up_swiglu=gemm_skinny_kernel<4, 4, 1> \
         [--json profiles/hbm_traffic_measured.json]
+    python bench_rocprof.py counters RUN_DIR [--match SUBSTRING ...]
 
 `trace` prints calls / average / min / max / total per kernel of a
 `rocprofv3 --kernel-trace --stats` run.  `traffic` reads one `--pmc FETCH_SIZE`
@@ -12,7 +13,9 @@ what it shows for the library's streaming copy of known size (which reads and
 writes exactly --copy-bytes), and prints HBM bytes per launch for every kernel;
 with --json it records the kernels named by --kernel (label=substring of the
 kernel name; several substrings joined by | are summed, for an operation made
-of several kernels) for bench.py's `roofline.traffic`.
+of several kernels) for bench.py's `roofline.traffic`.  `counters` prints the
+per-kernel average of every counter of a `--pmc` run (kernels whose name holds
+one of the --match substrings; all without).
 """
 from __future__ import annotations
 
@@ -109,6 +112,22 @@ def traffic(fetch_dir, write_dir, copy_bytes, workload, kernels, json_path):
             f.write("\n")
 
 
+def counters(run_dir, match):
+    cur = _db(run_dir).cursor()
+    rows = cur.execute("select kernel_name, counter_name, count(*), avg(value) from counters_collection "
+                       "group by kernel_name, counter_name").fetchall()
+    per = {}
+    for k, c, n, v in rows:
+        name = _short(k)
+        if match and not any(m.replace(" ", "") in name.replace(" ", "") for m in match):
+            continue
+        per.setdefault(name, {})[c] = (n, v)
+    for name in sorted(per):
+        print(name)
+        for c, (n, v) in sorted(per[name].items()):
+            print(f"   {c:32s} launches={n:5d} avg={v:16.1f}")
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -121,9 +140,14 @@ def main():
     p.add_argument("--workload", default="cfg2")
     p.add_argument("--kernel", action="append", default=[])
     p.add_argument("--json", default=None)
+    c = sub.add_parser("counters")
+    c.add_argument("run_dir")
+    c.add_argument("--match", action="append", default=[])
     a = ap.parse_args()
     if a.cmd == "trace":
         trace(a.run_dir)
+    elif a.cmd == "counters":
+        counters(a.run_dir, a.match)
     else:
         traffic(a.fetch_dir, a.write_dir, a.copy_bytes, a.workload, a.kernel, a.json)
 
