@@ -282,7 +282,7 @@ def run_decode(args, cfg_id):
             view.reset()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            view.prefill(emb, chunk)
+            view.prefill(emb, chunk, want_hidden=False)
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
         res["prefill"] = {"tokens": P, "chunk": chunk, "ms": round(1e3 * dt, 2),

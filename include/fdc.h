@@ -268,7 +268,9 @@ int32_t fdc_kv_append(fdc_ctx* ctx, int32_t layer, const void* k_new, const void
  *  tok_in      device int32 [B*R*T] input token ids, or NULL when emb_in given
  *  emb_in      device bf16 [B*R*T][d_model] input rows, or NULL
  *  tok_out     device int32 [B*R*T] greedy next token (lowest index among
- *              maxima), -1 for inactive rows
+ *              maxima), -1 for inactive rows; or NULL (gap_out and logits_out
+ *              NULL too): the rows only fill the cache, the LM head and the
+ *              argmax are not run (a prefill pass)
  *  gap_out     device fp32 [B*R*T] top-1 minus top-2 logit, or NULL
  *  logits_out  device fp32 [B*R*T][vocab], or NULL
  *  hidden_out  device fp32 [(L+2)][B*R*T][d_model], or NULL: residual stream

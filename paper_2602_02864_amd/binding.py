@@ -468,9 +468,10 @@ class Context:
         return Context(self.dims, [P] + [int(x) for x in self.slot_len], edges, 0, self.B, 1, max_tokens,
                        device=str(self.device), share=self)
 
-    def prefill(self, emb_rows, chunk: int):
+    def prefill(self, emb_rows, chunk: int, want_hidden: bool = True):
         """Causal prefill of field 0 of every scene from embedding rows [B][n][d]
-        (bf16 values), `chunk` tokens per pass; returns the last pass's outputs."""
+        (bf16 values), `chunk` tokens per pass; returns the last pass's outputs (the
+        only pass that runs the LM head: the others just fill the cache)."""
         torch = self.torch
         e = self._dev_bf16(emb_rows).reshape(self.B, -1, self.dims.d_model)
         n = e.shape[1]
@@ -479,7 +480,8 @@ class Context:
             T = min(chunk, n - t0)
             out = self.parallel_decode_step(np.zeros((self.B, 1), dtype=np.int32),
                                             np.full((self.B, 1), t0, dtype=np.int32),
-                                            emb_in=e[:, t0:t0 + T].contiguous(), T=T, want_hidden=True)
+                                            emb_in=e[:, t0:t0 + T].contiguous(), T=T, want_hidden=want_hidden,
+                                            want_tokens=t0 + T >= n)
         return out
 
     def close(self):
@@ -589,7 +591,9 @@ class Context:
 
     # -- the step -------------------------------------------------------------------
     def parallel_decode_step(self, branch_field, branch_off, tok_in=None, emb_in=None, T: int = 1,
-                             want_logits=False, want_hidden=False, want_gap=True) -> dict:
+                             want_logits=False, want_hidden=False, want_gap=True, want_tokens=True) -> dict:
+        """want_tokens=False (with no logits and no gaps): the rows only fill the cache, the
+        LM head and the argmax are not run (prefill passes)."""
         torch = self.torch
         bf, bo = _i32(branch_field), _i32(branch_off)
         assert bf.size == bo.size and bf.size % self.B == 0
@@ -605,8 +609,8 @@ class Context:
         if emb_in is not None:
             emb_t = self._dev_bf16(emb_in)
             assert emb_t.numel() == M * d.d_model
-        out = {"tok": torch.empty(M, dtype=torch.int32, device=dev)}
-        if want_gap:
+        out = {"tok": torch.empty(M, dtype=torch.int32, device=dev)} if want_tokens else {}
+        if want_gap and want_tokens:
             out["gap"] = torch.empty(M, dtype=torch.float32, device=dev)
         if want_logits:
             out["logits"] = torch.empty(M, d.vocab, dtype=torch.float32, device=dev)

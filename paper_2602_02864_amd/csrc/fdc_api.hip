@@ -848,7 +848,8 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     if (!c->kc || !c->vc || !c->ws || !c->emb || !c->gf || !c->lm) return fail(FDC_ESTATE, "cache, workspace or head weights not set");
     for (int l = 0; l < c->m.n_layers; ++l)
         if (!c->lw_set[l]) return fail(FDC_ESTATE, "weights of layer %d not set", l);
-    if (!tok_out) return fail(FDC_EINVAL, "tok_out is null");
+    if (!tok_out && (gap_out || logits_out))
+        return fail(FDC_EINVAL, "tok_out is null although logits or gaps are asked for");
     if ((tok_in == nullptr) == (emb_in == nullptr)) return fail(FDC_EINVAL, "give exactly one of tok_in and emb_in");
     int32_t rc = check_step(c, R, T, bf, bo, true);
     if (rc != FDC_OK) return rc;
@@ -1026,8 +1027,11 @@ int32_t fdc_parallel_decode_step(fdc_ctx* c, int32_t R, int32_t T, const int32_t
     gl.M = M;
     gl.N = m.vocab;
     gl.n_valid = m.vocab;
-    { ProfScope ps_(c, PK_LMHEAD, st); project(c->p_lm, m.vocab, d, EPI_PARTIAL, gl, true); }
-    { ProfScope ps_(c, PK_ARGMAX, st); launch_argmax(logits, M, m.vocab, m.vocab, tok_out, gap_out, sm.branch_field, T, st); }
+    // no tokens wanted (a prefill pass: the rows only fill the cache): no head
+    if (tok_out) {
+        { ProfScope ps_(c, PK_LMHEAD, st); project(c->p_lm, m.vocab, d, EPI_PARTIAL, gl, true); }
+        { ProfScope ps_(c, PK_ARGMAX, st); launch_argmax(logits, M, m.vocab, m.vocab, tok_out, gap_out, sm.branch_field, T, st); }
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !launched) {
         c->valid_len = saved;

@@ -313,7 +313,35 @@ def test_step_error_paths_leave_state_unchanged():
     with pytest.raises(FdcError) as e:
         ctx.parallel_decode_step([0], [0])                                 # neither tokens nor rows
     assert e.value.code == fb.FDC_EINVAL
+    with pytest.raises(FdcError) as e:                                     # logits of a pass that runs no head
+        ctx.parallel_decode_step([0], [0], tok_in=[0], want_logits=True, want_tokens=False)
+    assert e.value.code == fb.FDC_EINVAL
     assert np.array_equal(ctx.get_valid_len(), before)
+    pair.close()
+
+
+def test_pass_without_tokens_fills_the_cache_like_any_other():
+    """A pass that asks for no tokens (a prefill pass) skips the LM head and the
+    argmax; the residual stream it reports and the K/V it leaves are those of the
+    same pass with the head: the next step, which reads that K/V, matches the
+    oracle either way."""
+    import torch
+    dims = model_dims(0)
+    tpl = template(0)
+    w = draw_weights(0, dims, random_gains=True)
+    pair = Pair(dims, tpl, w)
+    _random_prefix_kv(pair, 0)
+    full = pair.ctx.parallel_decode_step([0, 1, 2], [0, 0, 0], tok_in=[5, 6, 7], want_hidden=True)
+    torch.cuda.synchronize()
+    h_full = full["hidden"].cpu().numpy()
+    pair.ctx.reset()
+    quiet = pair.ctx.parallel_decode_step([0, 1, 2], [0, 0, 0], tok_in=[5, 6, 7], want_hidden=True, want_tokens=False)
+    torch.cuda.synchronize()
+    assert "tok" not in quiet and np.array_equal(quiet["hidden"].cpu().numpy(), h_full)
+    # the oracle takes the same first step, then both take a second one on top of it
+    pair.dec.step(np.array([[0, 1, 2]], dtype=np.int32), np.array([[0, 0, 0]], dtype=np.int32),
+                  tok_in=np.array([5, 6, 7], dtype=np.int32).reshape(1, 3, 1))
+    pair.step_both([[0, 1, 2]], [[1, 1, 1]], [9, 10, 11], tag="after a pass without tokens")
     pair.close()
 
 
