@@ -229,6 +229,53 @@ def _cfg_head_weights(cfg_id, dims):
             "lm": draw_normal_bf16(rng, (dims.vocab, dims.d_model), 0.02)}
 
 
+def test_workload4_three_layers_two_passes_256_rows():
+    """Workload 4 at full width beyond one layer: three 7B-class layers, 8 scenes,
+    prefix 8192, the first level's 8 fields with 4 tokens per pass (256 rows, the
+    launch shape the benchmark times), two passes in a row - the second reads, in
+    every layer, the K/V the first one stored.  Mask and positions of all 256 rows
+    bit for bit; hidden states after every layer and logits against the oracle on
+    two of the eight scenes (scenes are independent)."""
+    import torch
+    dims = model_dims(4, n_layers=3)
+    tpl = template(4)
+    w = {"layers": [draw_layer_weights(4, dims, l, random_gains=True) for l in range(dims.n_layers)],
+         **_cfg_head_weights(4, dims)}
+    B, R, T = 8, 8, 4
+    sample = [2, 5]
+    pair = Pair(dims, tpl, w, n_scenes=B, max_branches=R, max_tokens=T)
+    sub = O.OracleDecoder(dims, w, tpl.prefix_len, tpl.slot_len, tpl.edges, len(sample), kv_bf16=True)
+    shp = (dims.n_layers, dims.n_kv_heads, tpl.prefix_len, dims.head_dim)
+    for b in range(B):
+        prng = workload_seed(4, "prefix", 70 + b)
+        K, V = draw_normal_bf16(prng, shp), draw_normal_bf16(prng, shp)
+        pair.install_prefix_kv(b, K, V)
+        if b in sample:
+            sub.set_prefix_kv(sample.index(b), K, V)
+    trng = np.random.default_rng(46)
+    bf = np.tile(np.arange(R, dtype=np.int32), (B, 1))
+    rows_g = np.concatenate([np.arange(b * R * T, (b + 1) * R * T) for b in sample])
+    L = dims.n_layers
+    for step in range(2):
+        bo = np.full((B, R), step * T, dtype=np.int32)
+        tok = trng.integers(0, dims.vocab, size=(B, R, T)).astype(np.int32)
+        g = pair.ctx.parallel_decode_step(bf, bo, tok_in=tok, T=T, want_logits=True, want_hidden=True)
+        torch.cuda.synchronize()
+        got = {k: v.cpu().numpy() for k, v in g.items() if not k.startswith("_")}
+        pair.dec.valid_len[:, :R] = (step + 1) * T
+        assert np.array_equal(pair.ctx.get_valid_len(), pair.dec.valid_len)
+        pair.compare_tables(bf, bo, T, f"cfg4 three layers, pass {step}")
+        ref = sub.step(bf[sample], bo[sample], tok_in=tok[sample], T=T)
+        errs = [rel_err(got["hidden"][l][rows_g], ref["hidden"][l]) for l in range(L + 1)]
+        errs.append(rel_err(got["hidden"][L + 1][rows_g], ref["normed"]))
+        errs.append(rel_err(got["logits"][rows_g], ref["logits"]))
+        assert max(errs) <= ARITH_BOUND, (step, errs)
+        sure = np.nonzero(ref["gap"] > 1e-2)[0]
+        assert sure.size > 0
+        assert np.array_equal(got["tok"][rows_g][sure], ref["tok"][sure])
+    pair.close(need_sure=False)
+
+
 def test_workload4_all_active_1024_rows_full_width():
     """The all-active half of workload 4 at full width, in the launch shape the
     benchmark's stress run times: 8 scenes x 32 fields x 4 tokens = 1024 rows
