@@ -222,11 +222,12 @@ def _wide_slots_template(n_fields=24, slot=64, prefix_len=100, p=0.2, seed=3):
     return Template(prefix_len, [slot] * n_fields, edges, [slot] * n_fields, [1] * n_fields, name="wide")
 
 
-@pytest.mark.parametrize("variant", ["0", "1"])
+@pytest.mark.parametrize("variant", ["0", "1", "2"])
 @pytest.mark.parametrize("B,T", [(1, 1), (2, 2)])
 def test_masked_attention_with_more_than_32_slot_tiles(monkeypatch, variant, B, T):
     """48 tiles reach past the prefix: more than one workgroup's mask tables hold
-    (32), so the chunks are cut shorter; under both attention kernels."""
+    (32), so the chunks are cut shorter; under all three attention kernels (the
+    many-row kernel then keeps the context's cut instead of the step's own)."""
     from paper_2602_02864_amd import fdc_attention_plan
     monkeypatch.setenv("FDC_ATTN_VARIANT", variant)
     dims = ATT_DIMS["g4d128"]
