@@ -689,7 +689,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path's sharding is described in DESIGN.md)", file=sys.stderr)
+              "(scenes, then KV heads and MLP columns, are how the path would shard; none of it is built)",
+              file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
