@@ -19,7 +19,10 @@
 //     fp16 (the bf16 values times 2^8: exact, fdc_pack_weight), the activations come
 //     as single fp16 fragments (11 significant bits) instead of a bf16 head + tail:
 //     one matrix instruction per weight fragment instead of two and half the row
-//     traffic; the epilogue takes the 2^8 out again.
+//     traffic; the epilogue takes the 2^8 out again.  The eight-wavefront F16 kernels
+//     bring the weights through LDS too (asynchronous copies straight into a
+//     four-stage ring, operands of the next k tile read during the matrix work of
+//     this one).
 #include "kernels_common.hpp"
 #include "fdc_launch.hpp"
 
@@ -253,7 +256,27 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a, TiledPlan p
 // in neighbouring wavefronts: the SwiGLU epilogue passes that one tile through
 // LDS.  (A 4 x 2 grid needs no such exchange but asks the L1 for every weight
 // line four times and measured slower than the four-wavefront kernel.)
-template <int NTW, int EPI, int WM, bool F16>
+// waits until at most n LDS reads of this wavefront are outstanding (n is a constant
+// after unrolling)
+__device__ __forceinline__ void wait_lds_reads(int n) {
+    switch (n) {
+        case 0: asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt lgkmcnt(1)" ::: "memory"); break;
+        case 2: asm volatile("s_waitcnt lgkmcnt(2)" ::: "memory"); break;
+        case 3: asm volatile("s_waitcnt lgkmcnt(3)" ::: "memory"); break;
+        case 4: asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory"); break;
+        case 5: asm volatile("s_waitcnt lgkmcnt(5)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); break;
+    }
+}
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef const __attribute__((address_space(1))) void glb_void_t;
+
+// LW: the weight fragments go through the LDS ring as well (asynchronous copies
+// straight into LDS, four stages), so that each is fetched once per workgroup and
+// not once by each of the WM wavefronts that use it.
+template <int NTW, int EPI, int WM, bool F16, bool LW = false>
 __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan p) {
     constexpr int NFA = F16 ? kWgMTiles : 2 * kWgMTiles;   // row fragments per k tile: heads (, tails)
     constexpr int NSRC = F16 ? 1 : 2;
@@ -261,7 +284,9 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
     constexpr int MF = kWgMTiles / WM;                 // 16-row fragments per wavefront
     constexpr int TW = 2 * NTW / WN;                   // 16-feature tiles per wavefront
     static_assert(2 * NTW % WN == 0, "feature tiles must divide over the wavefronts");
-    __shared__ uint4 lds[kStages][NFA][64];
+    constexpr int NPC = NFA + 2 * NTW;                 // LW: 1 KiB pieces per k tile (rows, then weights)
+    constexpr int kRing = LW ? 4 : kStages;
+    __shared__ uint4 lds[kRing][LW ? NPC : NFA][64];
 
     // the wavefront's index as a scalar: what follows from it (tile numbers, base
     // addresses) then lives in scalar registers, and the loads take a scalar base
@@ -343,7 +368,109 @@ __global__ __launch_bounds__(512) void gemm_tiled8_kernel(GemmArgs a, TiledPlan 
         lds_barrier();                                                                     \
         stg = stg == 2 ? 0 : stg + 1;                                                      \
     }
-    if (nkt > 0) {
+    if constexpr (LW) {
+        // piece q of a k tile: q < NFA a row fragment (heads, then tails), else weight
+        // tile q - NFA of the group; wavefront w copies pieces w, w + 8, ...
+        constexpr int NPJ = (NPC + 7) / 8;
+        const uint16_t* psrc[NPJ];
+#pragma unroll
+        for (int j = 0; j < NPJ; ++j) {
+            const int q = wave + 8 * j;
+            if (q < NFA) {
+                const int mt = min(mb * kWgMTiles + (q % kWgMTiles), p.m_tiles - 1);
+                psrc[j] = ((q >= kWgMTiles) ? a.act_lo : a.act_hi) + ((size_t)mt * p.KT + kt0) * 512;
+            } else {
+                const int tile = min(ng * 2 * NTW + (q - NFA), p.n_tiles - 1);
+                psrc[j] = a.w + ((size_t)tile * p.KT + kt0) * 512;
+            }
+        }
+        const bool full = wave + 8 * (NPJ - 1) < NPC;      // this wavefront copies NPJ pieces, else NPJ - 1
+        auto issue = [&](int i, int stg) {
+            if (i >= nkt) return;
+#pragma unroll
+            for (int j = 0; j < NPJ; ++j) {
+                const int q = wave + 8 * j;
+                if (q < NPC)
+                    __builtin_amdgcn_global_load_lds((glb_void_t*)(psrc[j] + (size_t)i * 512 + lane * 8),
+                                                     (lds_void_t*)&lds[stg][q][0], 16, 0, 0);
+            }
+        };
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t*)&lds[0][0][0] + lane * 16;
+        auto rd = [&](f32x4& d, uint32_t off) { asm volatile("ds_read_b128 %0, %1" : "=v"(d) : "v"(off)); };
+        // Operands of k tile i are read from LDS during the matrix work of tile i - 1
+        // (two register sets), so that no tile starts with a wait for LDS.
+        f32x4 rh[2][MF], rl[2][F16 ? 1 : MF], wb[2][TW];
+        auto fetch_ops = [&](int set, int stg) {
+            const uint32_t base = lds0 + stg * (NPC * 1024);
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) rd(rh[set][mf], base + (MF * wm + mf) * 1024);
+            if (!F16) {
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf) rd(rl[set][mf], base + (NFA / 2 + MF * wm + mf) * 1024);
+            }
+#pragma unroll
+            for (int t = 0; t < TW; ++t) rd(wb[set][t], base + (NFA + wn * TW + t) * 1024);
+        };
+        auto wait_mine = [&](int ahead) {            // my copies: all but those of the `ahead` youngest tiles have landed
+            if (full) {
+                if (ahead >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * NPJ) : "memory");
+                else if (ahead == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NPJ) : "memory");
+                else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NPJ) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            } else {
+                if (ahead >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * (NPJ - 1)) : "memory");
+                else if (ahead == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (NPJ - 1)) : "memory");
+                else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NPJ - 1) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+        };
+        auto mma_tile = [&](int set) {
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                asm volatile("" : "+v"(rh[set][mf]));
+                if (!F16) asm volatile("" : "+v"(rl[set][mf]));
+            }
+#pragma unroll
+            for (int t = 0; t < TW; ++t) {
+                asm volatile("" : "+v"(wb[set][t]));
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf) {
+                    acc[mf][t] = mma16<F16>(wb[set][t], __builtin_bit_cast(uint4, rh[set][mf]), acc[mf][t]);
+                    if (!F16) acc[mf][t] = mma16<F16>(wb[set][t], __builtin_bit_cast(uint4, rl[set][mf]), acc[mf][t]);
+                }
+            }
+        };
+        if (nkt > 0) {
+            issue(0, 0);
+            issue(1, 1);
+            issue(2, 2);
+            issue(3, 3);
+            // tile 0 into the first operand set
+            wait_mine(min(nkt - 1, 3));
+            asm volatile("s_barrier" ::: "memory");
+            fetch_ops(0, 0);
+            // iteration i: tile i's operands are (being) read into set i % 2; tiles i + 1 .. i + 3 in flight
+            auto iter = [&](int i, int set) {
+                // tile i's operands are in registers (for every wavefront once it passes the barrier)
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (i + 1 < nkt) {
+                    wait_mine(min(nkt - 2 - i, 2));              // my copies of tile i + 1 have landed
+                    asm volatile("s_barrier" ::: "memory");     // everyone's have; stage i % 4 is free
+                    issue(i + 4, i & 3);
+                    fetch_ops(set ^ 1, (i + 1) & 3);
+                }
+                mma_tile(set);
+            };
+            int i = 0;
+            for (; i + 1 < nkt; i += 2) {
+                iter(i, 0);
+                iter(i + 1, 1);
+            }
+            if (i < nkt) iter(i, 0);
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        }
+        asm volatile("s_barrier" ::: "memory");          // the ring is free (the epilogue may use it)
+    } else if (nkt > 0) {
         FDC_FETCH(g0, 0);
         FDC_FETCH(g1, 1);
         _Pragma("unroll") for (int t = 0; t < TW; ++t) FDC_FETCHW1(b0, t, 0);
@@ -452,10 +579,15 @@ template <int NTW, bool F16>
 void launch_ntw(const TiledPlan& p, int epilogue, const GemmArgs& a, hipStream_t st) {
     const dim3 grid(p.grid);
     if (NTW >= 8) {
+        // Single-pass fp16 kernels take the weights through LDS (measured: LM head 88 ->
+        // 72 us, gate/up 97 -> 84 us at 256 rows): they are bound by what a compute unit
+        // can fetch, and each weight fragment is then fetched once per workgroup.  The
+        // two-pass kernels read twice as many row fragments from LDS per k tile and
+        // measured 3 % slower that way, so they keep the weights in registers.
         if (epilogue == EPI_SWIGLU)
-            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_SWIGLU, 2, F16>), grid, dim3(512), 0, st, a, p);
+            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_SWIGLU, 2, F16, F16>), grid, dim3(512), 0, st, a, p);
         else
-            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_PARTIAL, 2, F16>), grid, dim3(512), 0, st, a, p);
+            hipLaunchKernelGGL((gemm_tiled8_kernel<NTW, EPI_PARTIAL, 2, F16, F16>), grid, dim3(512), 0, st, a, p);
     } else {
         if (epilogue == EPI_SWIGLU)
             hipLaunchKernelGGL((gemm_tiled_kernel<NTW, EPI_SWIGLU, F16>), grid, dim3(256), 0, st, a, p);
