@@ -24,7 +24,10 @@ def _torch():
                                    (256, 3584, 4864), (64, 37888, 512), (1000, 256, 160),
                                    # wide tiles (the eight-wavefront kernel): ragged rows, a feature count
                                    # that ends inside a tile and inside a workgroup, odd and even k tiles
-                                   (130, 20008, 288), (300, 33000, 96), (1000, 9000, 160), (513, 40000, 32)])
+                                   (130, 20008, 288), (300, 33000, 96), (1000, 9000, 160), (513, 40000, 32),
+                                   # the 7B-class projections at 256 and 1024 rows: wide tiles with K split
+                                   # nine ways (down), two ways over the 320-wide tile (QKV), two ways (O)
+                                   (256, 3584, 18944), (1024, 4608, 3584), (1024, 3584, 3584)])
 def test_linear_matches_fp64_matmul(M, N, K):
     """y = x W^T with bf16 weights; x is carried as bf16 head + tail, so the
     result must be fp32-accurate, far inside the 2e-3 budget."""
