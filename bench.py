@@ -27,7 +27,8 @@ Prints ONE JSON line.
   * `templates` (Sec. 4.3 of the paper): three dependency graphs over the same
     fields and token budget, each decoded in parallel, against autoregressive
     decoding of the same tokens (a chain-shaped graph): time against
-    critical-path length, speed-up against average parallel degree.
+    critical-path length, speed-up against average parallel degree; `ar_baseline`
+    is its summary (autoregressive rate and the three speed-ups).
   * `cpu_baseline` is the fp64 oracle timed on this host's cores on a bounded
     sample.
 """
@@ -267,6 +268,14 @@ def run_decode(args, cfg_id):
     }
     if not args.no_ar:
         res["templates"] = run_templates(torch, dims, tpl, dec, sched)
+        # the same comparison in one glance: autoregressive decoding of the same text
+        # against each of the three graphs
+        t = res["templates"]
+        res["ar_baseline"] = {
+            "tokens_per_s": t["autoregressive"]["tokens_per_s"], "passes": t["autoregressive"]["passes"],
+            "vs_parallel": [{"graph": g["graph"], "critical_path_passes": g["critical_path_passes"],
+                             "average_parallel_degree": g["average_parallel_degree"],
+                             "speedup": g["speedup_over_autoregressive"]} for g in t["parallel"]]}
     if not args.no_driver and args.steps == 0:
         res["driver"] = run_driver(ctx, dims, tpl, torch)
     if args.prefill:
