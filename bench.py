@@ -517,6 +517,7 @@ def measured_traffic(workload, kernel):
             return None, "no stored counter record for this kernel"
         return rec["bytes_per_launch"], ("stored rocprofv3 --pmc record (profiles/hbm_traffic_measured.json"
                                          + (f", {rec['recorded']}" if "recorded" in rec else "")
+                                         + (f", {rec['date']}" if "date" in rec else "")
                                          + "), not measured in this run")
     except (OSError, ValueError, KeyError):
         return None, "no stored counter record"
